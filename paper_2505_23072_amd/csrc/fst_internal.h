@@ -1,0 +1,140 @@
+// Internal structures shared by the host parts (parser, planner, stager) and the kernel launcher.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <string>
+#include <unordered_map>
+#include <utility>
+#include <vector>
+
+#include "fst.h"
+
+namespace fst {
+
+int fail(int status, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+struct Tensor {
+    std::string name;
+    int32_t dtype = 0;
+    int32_t ndim = 0;
+    uint64_t shape[FST_MAX_DIMS] = {};
+    uint64_t begin = 0, end = 0;
+};
+
+}  // namespace fst
+
+struct fst_header {
+    uint64_t n_json = 0;
+    uint64_t file_size = 0;
+    std::vector<fst::Tensor> tensors;                      // ordered by offset
+    std::unordered_map<std::string, size_t> index;          // name -> position in `tensors`
+    std::vector<std::pair<std::string, std::string>> metadata;
+};
+
+namespace fst {
+
+// How a descriptor's rows are moved.  The vector path moves whole chunks (16 bytes when nothing
+// is converted, 8 elements otherwise); the element path moves single elements and serves ragged
+// tails and rows whose byte length is not a whole number of chunks.
+enum Path : uint32_t { PATH_VEC = 0, PATH_ELEM = 1 };
+
+// Conversion kinds (Section III-B).  COPY moves bytes and ignores the element type.
+enum Conv : uint32_t { CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CONV_F2H, CONV_F2B, CONV_COUNT };
+
+// One unit of kernel work, as uploaded to the device (64 bytes).
+struct DevDesc {
+    uint64_t src_off;        // byte offset of row 0, relative to the resident raw buffer
+    uint64_t src_stride;     // bytes between rows
+    uint64_t dst;            // device address of the first output byte of this piece
+    uint64_t n_units;        // VEC: chunks in total (rows * units_per_row); ELEM: elements
+    uint32_t units_per_row;  // VEC: chunks per row; ELEM: elements per row
+    uint32_t tile0;          // index of this piece's first tile inside its launch
+    uint32_t n_tiles;
+    uint32_t pad0;
+    uint64_t pad1, pad2;
+};
+static_assert(sizeof(DevDesc) == 64, "DevDesc is 64 bytes");
+
+// Host-side piece: a DevDesc minus the output address, plus bookkeeping.
+struct Piece {
+    uint32_t output = 0;
+    uint32_t path = PATH_VEC;
+    uint32_t conv = CONV_COPY;
+    bool dword_aligned = true;   // every chunk source address is a multiple of 4
+    uint64_t src_file_off = 0;   // file offset of row 0
+    uint64_t src_stride = 0;
+    uint64_t dst_off = 0;        // byte offset inside the output
+    uint64_t n_units = 0;
+    uint32_t units_per_row = 0;
+    uint64_t src_span = 0;       // bytes from row 0 start to the end of the last row
+    uint64_t read_bytes = 0, write_bytes = 0;
+};
+
+struct Group {
+    uint32_t file = 0;
+    uint64_t lo = 0, hi = 0;
+    size_t desc_begin = 0, desc_end = 0;    // public descriptors [begin, end)
+    std::vector<Piece> pieces;              // sorted by launch class
+    uint64_t read_bytes = 0, write_bytes = 0;
+};
+
+struct Output {
+    fst_output_info info;
+    // geometry of the request, kept so that groups can be re-cut
+    int32_t src_dtype = 0;
+    uint64_t src_file_off = 0;   // file offset of row 0 of the rank's share
+    uint64_t src_stride = 0;
+    uint64_t row_elems = 0;
+    uint64_t n_rows = 0;
+    uint64_t tensor_begin = 0;   // file offset of the stored tensor (for ordering)
+};
+
+// Launch classes: (conv, byte-aligned?) for the vector path, then one class for the element path.
+constexpr uint32_t N_CLASSES = CONV_COUNT * 2 + CONV_COUNT;
+inline uint32_t launch_class(const Piece &p)
+{
+    return p.path == PATH_VEC ? p.conv * 2 + (p.dword_aligned ? 0 : 1) : CONV_COUNT * 2 + p.conv;
+}
+
+// Geometry of the kernels, fixed at compile time and needed by the planner to count tiles.
+constexpr uint32_t BLOCK_THREADS = 256;
+constexpr uint32_t VEC_UNROLL = 4;                       // chunks in flight per thread
+constexpr uint32_t VEC_ITERS = 4;                        // unrolled batches per tile
+constexpr uint32_t VEC_TILE_UNITS = BLOCK_THREADS * VEC_UNROLL * VEC_ITERS;   // chunks per tile
+constexpr uint32_t ELEM_TILE_UNITS = BLOCK_THREADS * 16;                      // elements per tile
+
+uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
+uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)
+uint32_t conv_dst_bytes(uint32_t conv);
+uint32_t conv_chunk_elems(uint32_t conv);                     // 16 (bytes) for COPY, 8 otherwise
+
+}  // namespace fst
+
+struct fst_plan {
+    size_t n_files = 0;
+    std::vector<uint64_t> raw_base;
+    std::vector<uint64_t> file_size;
+    std::vector<fst::Output> outputs;
+    std::vector<fst_descriptor> descs;        // public view, grouped
+    std::vector<fst::Group> groups;
+    uint64_t read_bytes = 0, write_bytes = 0;
+    size_t max_group_pieces = 0;
+    size_t total_pieces = 0;
+};
+
+namespace fst {
+int build_groups(fst_plan *p, uint64_t max_group_bytes);
+
+// One kernel launch: pieces [first, first+count) of a device table, all of one launch class.
+struct LaunchRange { uint32_t cls, first, count, tiles; };
+// Device table for groups [g0, g1) merged into one launch set.  slot: address sources for the
+// slot layout of group g0 (then g1 == g0+1); bias is what to add to the source pointer.
+int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
+                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges, int64_t &bias);
+int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev,
+                  int64_t bias, void *stream);
+// Launch the kernels of one class.  descs_dev: the class's DevDesc array on the device.
+int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
+                         const void *raw_dev, int64_t src_bias, void *stream);
+}  // namespace fst

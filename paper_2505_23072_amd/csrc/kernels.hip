@@ -1,0 +1,348 @@
+// gfx950 kernels that turn raw safetensors bytes in HBM into typed, aligned tensors (paper
+// Section III-B: alignment fix and type conversion done in one pass on the GPU; one rank's
+// partition is taken in the same pass).  Pure data movement: HBM-bound, no matrix cores.
+//
+// Work is a table of pieces (DevDesc).  One workgroup of 256 threads = 4 wavefronts takes one
+// tile of a piece; the piece is found by a binary search over the table's tile prefix, done with
+// scalar loads since it only depends on the workgroup index.  In the vector path a lane moves one
+// chunk at a time: 16 source bytes when nothing is converted, 8 elements otherwise, always
+// written with full 16-byte stores to a 16-byte aligned destination.  Several chunks per lane are
+// loaded before the first store so that enough reads are in flight to cover HBM latency.
+//
+// The source may start at any byte.  Sources that are a multiple of 4 are read with 4-byte
+// aligned 16-byte loads.  Others read the enclosing aligned dwords (one more than the chunk
+// holds) and shift them into place with v_alignbyte_b32, so every load stays dword aligned and
+// no byte outside the dwords that hold requested bytes is touched.
+#include <hip/hip_runtime.h>
+
+#include "fst_internal.h"
+
+namespace fst {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));      // 16 bytes at a 4-byte aligned address
+// Everything the kernels touch is global memory; saying so keeps the compiler from emitting flat
+// (generic address space) accesses for pointers it cannot trace back to a kernel argument.
+#define FST_GLOBAL __attribute__((address_space(1)))
+
+__device__ __forceinline__ u32x4 gload16(const void *p)
+{
+    return *(const FST_GLOBAL u32x4_a4 *)(p);
+}
+__device__ __forceinline__ uint32_t gload4(const void *p)
+{
+    return *(const FST_GLOBAL uint32_t *)(p);
+}
+__device__ __forceinline__ void gstore16(void *p, u32x4 v)
+{
+    *(FST_GLOBAL u32x4 *)(p) = v;
+}
+
+struct Chunk32 { u32x4 lo, hi; };                        // up to 32 source or result bytes
+
+__device__ __forceinline__ uint32_t shift_bytes(uint32_t hi, uint32_t lo, uint32_t sh)
+{
+    return __builtin_amdgcn_alignbyte(hi, lo, sh);       // ({hi,lo} >> 8*sh)[31:0], sh in 0..3
+}
+
+// 16 bytes from any address (BYTE) or from a 4-byte aligned one.
+template <bool BYTE>
+__device__ __forceinline__ u32x4 load16(const uint8_t *src)
+{
+    if (!BYTE) return gload16(src);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(src);
+    const uint32_t sh = uint32_t(a) & 3u;
+    const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
+    const u32x4 v = gload16(p);
+    const uint32_t e = sh ? gload4(p + 16) : 0u;         // the fifth dword only if it holds wanted bytes
+    u32x4 r;
+    r.x = shift_bytes(v.y, v.x, sh);
+    r.y = shift_bytes(v.z, v.y, sh);
+    r.z = shift_bytes(v.w, v.z, sh);
+    r.w = shift_bytes(e, v.w, sh);
+    return r;
+}
+
+template <bool BYTE>
+__device__ __forceinline__ Chunk32 load32(const uint8_t *src)
+{
+    Chunk32 c;
+    if (!BYTE) {
+        c.lo = gload16(src);
+        c.hi = gload16(src + 16);
+        return c;
+    }
+    const uintptr_t a = reinterpret_cast<uintptr_t>(src);
+    const uint32_t sh = uint32_t(a) & 3u;
+    const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
+    const u32x4 v = gload16(p);
+    const u32x4 w = gload16(p + 16);
+    const uint32_t e = sh ? gload4(p + 32) : 0u;
+    c.lo.x = shift_bytes(v.y, v.x, sh);
+    c.lo.y = shift_bytes(v.z, v.y, sh);
+    c.lo.z = shift_bytes(v.w, v.z, sh);
+    c.lo.w = shift_bytes(w.x, v.w, sh);
+    c.hi.x = shift_bytes(w.y, w.x, sh);
+    c.hi.y = shift_bytes(w.z, w.y, sh);
+    c.hi.z = shift_bytes(w.w, w.z, sh);
+    c.hi.w = shift_bytes(e, w.w, sh);
+    return c;
+}
+
+// ---- element conversions on bit patterns: round to nearest even, overflow to infinity, gradual
+// underflow, sign of zero kept; NaN keeps sign and leading payload bits and is made quiet.
+
+// binary16 -> binary32 (exact).  Subnormals: the 10-bit field m stands for m * 2^-24, which the
+// int->float conversion and one exact multiplication produce without a normalisation loop.
+__device__ __forceinline__ uint32_t half_to_float(uint32_t h)
+{
+    const uint32_t sign = (h & 0x8000u) << 16;
+    const uint32_t mag = h & 0x7FFFu;
+    uint32_t r = (mag << 13) + 0x38000000u;                              // normal: rebias 15 -> 127
+    if (mag < 0x0400u) r = __float_as_uint(float(mag) * 0x1p-24f);       // zero and subnormals
+    if (mag >= 0x7C00u) r = (mag << 13) | 0x7F800000u | ((mag & 0x3FFu) ? 0x00400000u : 0u);
+    return sign | r;
+}
+
+// bfloat16 -> binary32: the same bits, 16 places up.
+__device__ __forceinline__ uint32_t bfloat_to_float(uint32_t b)
+{
+    const uint32_t r = b << 16;
+    return ((r & 0x7FFFFFFFu) > 0x7F800000u) ? (r | 0x00400000u) : r;
+}
+
+// binary32 -> bfloat16: add half an ulp of the result (minus one when the kept lsb is even) and
+// truncate; the carry out of the mantissa moves the exponent up, through to infinity.
+__device__ __forceinline__ uint32_t float_to_bfloat(uint32_t x)
+{
+    const uint32_t rounded = (x + 0x7FFFu + ((x >> 16) & 1u)) >> 16;
+    const uint32_t nan = (x >> 16) | 0x0040u;
+    return ((x & 0x7FFFFFFFu) > 0x7F800000u) ? nan : rounded;
+}
+
+// binary32 -> binary16.
+__device__ __forceinline__ uint32_t float_to_half(uint32_t x)
+{
+    const uint32_t sign = (x >> 16) & 0x8000u;
+    const uint32_t mag = x & 0x7FFFFFFFu;
+    uint32_t r;
+    if (mag >= 0x38800000u) {
+        // normal result: rebias, round the 13 dropped bits, clamp everything from 65520 up to inf
+        const uint32_t t = mag - 0x38000000u;
+        r = (t + 0x0FFFu + ((t >> 13) & 1u)) >> 13;
+        if (mag >= 0x477FF000u) r = 0x7C00u;
+        if (mag > 0x7F800000u) r = 0x7E00u | ((mag >> 13) & 0x1FFu);
+    } else {
+        // |x| < 2^-14: adding 0.5 lines the value up so that the sum's low mantissa bits are
+        // x / 2^-24 rounded to nearest even by the adder itself (ulp of [0.5, 1) is 2^-24)
+        r = __float_as_uint(__uint_as_float(mag) + 0.5f) - 0x3F000000u;
+    }
+    return sign | r;
+}
+
+template <uint32_t CONV> struct ConvTraits;
+template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16; };
+template <> struct ConvTraits<CONV_H2B> { static constexpr uint32_t SRC = 16, DST = 16; };
+template <> struct ConvTraits<CONV_B2H> { static constexpr uint32_t SRC = 16, DST = 16; };
+template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 16, DST = 32; };
+template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 16, DST = 32; };
+template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DST = 16; };
+template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16; };
+
+template <uint32_t CONV>
+__device__ __forceinline__ uint32_t convert_bits(uint32_t v)
+{
+    if (CONV == CONV_H2B) return float_to_bfloat(half_to_float(v));     // one rounding: widening is exact
+    if (CONV == CONV_B2H) return float_to_half(bfloat_to_float(v));
+    if (CONV == CONV_H2F) return half_to_float(v);
+    if (CONV == CONV_B2F) return bfloat_to_float(v);
+    if (CONV == CONV_F2H) return float_to_half(v);
+    if (CONV == CONV_F2B) return float_to_bfloat(v);
+    return v;
+}
+
+template <uint32_t CONV>
+__device__ __forceinline__ uint32_t narrow_pair(uint32_t packed)       // two 16-bit -> two 16-bit
+{
+    return convert_bits<CONV>(packed & 0xFFFFu) | (convert_bits<CONV>(packed >> 16) << 16);
+}
+
+// One chunk: 8 elements (or 16 raw bytes) in, converted out.
+template <uint32_t CONV>
+__device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
+{
+    Chunk32 o;
+    if (CONV == CONV_COPY) {
+        o.lo = in.lo;
+    } else if (CONV == CONV_H2B || CONV == CONV_B2H) {
+        o.lo.x = narrow_pair<CONV>(in.lo.x);
+        o.lo.y = narrow_pair<CONV>(in.lo.y);
+        o.lo.z = narrow_pair<CONV>(in.lo.z);
+        o.lo.w = narrow_pair<CONV>(in.lo.w);
+    } else if (CONV == CONV_H2F || CONV == CONV_B2F) {
+        o.lo.x = convert_bits<CONV>(in.lo.x & 0xFFFFu);
+        o.lo.y = convert_bits<CONV>(in.lo.x >> 16);
+        o.lo.z = convert_bits<CONV>(in.lo.y & 0xFFFFu);
+        o.lo.w = convert_bits<CONV>(in.lo.y >> 16);
+        o.hi.x = convert_bits<CONV>(in.lo.z & 0xFFFFu);
+        o.hi.y = convert_bits<CONV>(in.lo.z >> 16);
+        o.hi.z = convert_bits<CONV>(in.lo.w & 0xFFFFu);
+        o.hi.w = convert_bits<CONV>(in.lo.w >> 16);
+    } else {
+        o.lo.x = convert_bits<CONV>(in.lo.x) | (convert_bits<CONV>(in.lo.y) << 16);
+        o.lo.y = convert_bits<CONV>(in.lo.z) | (convert_bits<CONV>(in.lo.w) << 16);
+        o.lo.z = convert_bits<CONV>(in.hi.x) | (convert_bits<CONV>(in.hi.y) << 16);
+        o.lo.w = convert_bits<CONV>(in.hi.z) | (convert_bits<CONV>(in.hi.w) << 16);
+    }
+    return o;
+}
+
+// The piece that owns tile `b`: last entry whose first tile is <= b.
+__device__ __forceinline__ uint32_t find_piece(const DevDesc *__restrict__ descs, uint32_t n_desc, uint32_t b)
+{
+    uint32_t lo = 0, hi = n_desc;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (descs[mid].tile0 <= b) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// One tile: chunk i of the tile (i < n) is read at `src` + its row/column offset and written at
+// dst + i*CD.  FULL: the tile has all VEC_TILE_UNITS chunks, so no lane needs a bounds check.
+template <uint32_t CONV, bool BYTE, bool FULL>
+__device__ __forceinline__ void vec_tile(const uint8_t *src, uint8_t *dst, uint32_t n, uint32_t upr, uint32_t col0,
+                                         uint64_t stride)
+{
+    constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
+    for (uint32_t base = 0; base < (FULL ? VEC_TILE_UNITS : n); base += BLOCK_THREADS * VEC_UNROLL) {
+        Chunk32 v[VEC_UNROLL];
+#pragma unroll
+        for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
+            const uint32_t i = base + u * BLOCK_THREADS + threadIdx.x;
+            if (FULL || i < n) {
+                const uint8_t *s;
+                if (upr == 0) {
+                    s = src + uint64_t(i) * CS;
+                } else {
+                    const uint32_t cc = col0 + i;                        // chunk index from the row start
+                    const uint32_t r = cc / upr;
+                    s = src + uint64_t(r) * stride + uint64_t(cc - r * upr) * CS;
+                }
+                if (CS == 16) v[u].lo = load16<BYTE>(s); else v[u] = load32<BYTE>(s);
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
+            const uint32_t i = base + u * BLOCK_THREADS + threadIdx.x;
+            if (FULL || i < n) {
+                const Chunk32 o = convert_chunk<CONV>(v[u]);
+                uint8_t *t = dst + uint64_t(i) * CD;
+                gstore16(t, o.lo);
+                if (CD == 32) gstore16(t + 16, o.hi);
+            }
+        }
+    }
+}
+
+template <uint32_t CONV, bool BYTE>
+__global__ __launch_bounds__(BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs, uint32_t n_desc,
+                                                                 const uint8_t *__restrict__ raw)
+{
+    constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
+    const uint32_t b = blockIdx.x;
+    const DevDesc *d = descs + find_piece(descs, n_desc, b);
+    const uint64_t c0 = uint64_t(b - d->tile0) * VEC_TILE_UNITS;        // first chunk of this tile
+    const uint64_t left = d->n_units - c0;
+    const uint32_t n = left < VEC_TILE_UNITS ? uint32_t(left) : VEC_TILE_UNITS;
+    const uint32_t upr = d->units_per_row;
+    const uint64_t stride = d->src_stride;
+    uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + c0 * CD;
+    const uint8_t *src = raw + d->src_off;
+    uint32_t col0 = 0;
+    if (upr == 0) {
+        src += c0 * CS;                                                  // one row of any length
+    } else {
+        const uint64_t row0 = c0 / upr;
+        col0 = uint32_t(c0 - row0 * upr);
+        src += row0 * stride;
+    }
+
+    if (n == VEC_TILE_UNITS)
+        vec_tile<CONV, BYTE, true>(src, dst, n, upr, col0, stride);
+    else
+        vec_tile<CONV, BYTE, false>(src, dst, n, upr, col0, stride);
+}
+
+// Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
+// byte when nothing is converted) per thread and step; sources are read bytewise.
+template <uint32_t CONV>
+__global__ __launch_bounds__(BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs, uint32_t n_desc,
+                                                                  const uint8_t *__restrict__ raw)
+{
+    constexpr uint32_t ES = CONV == CONV_COPY ? 1 : (CONV == CONV_F2H || CONV == CONV_F2B) ? 4 : 2;
+    constexpr uint32_t ED = CONV == CONV_COPY ? 1 : (CONV == CONV_H2F || CONV == CONV_B2F) ? 4 : 2;
+    const uint32_t b = blockIdx.x;
+    const DevDesc *d = descs + find_piece(descs, n_desc, b);
+    const uint64_t e0 = uint64_t(b - d->tile0) * ELEM_TILE_UNITS;
+    const uint64_t left = d->n_units - e0;
+    const uint32_t n = left < ELEM_TILE_UNITS ? uint32_t(left) : ELEM_TILE_UNITS;
+    const uint32_t upr = d->units_per_row;
+    const uint64_t row0 = e0 / upr;
+    const uint32_t col0 = uint32_t(e0 - row0 * upr);
+    const uint8_t *src = raw + d->src_off + row0 * d->src_stride;
+    uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + e0 * ED;
+    for (uint32_t i = threadIdx.x; i < n; i += BLOCK_THREADS) {
+        const uint64_t cc = uint64_t(col0) + i;
+        const uint64_t r = cc / upr;
+        const uint8_t *s = src + r * d->src_stride + (cc - r * upr) * ES;
+        uint32_t v = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < ES; ++k) v |= uint32_t(*(const FST_GLOBAL uint8_t *)(s + k)) << (8 * k);
+        v = convert_bits<CONV>(v);
+        uint8_t *t = dst + uint64_t(i) * ED;
+        if (ED == 1) *(FST_GLOBAL uint8_t *)(t) = uint8_t(v);
+        else if (ED == 2) *(FST_GLOBAL uint16_t *)(t) = uint16_t(v);
+        else *(FST_GLOBAL uint32_t *)(t) = v;
+    }
+}
+
+template <uint32_t CONV>
+int launch_conv(uint32_t variant, const DevDesc *descs, uint32_t n_desc, uint32_t n_tiles, const uint8_t *raw,
+                hipStream_t stream)
+{
+    const dim3 grid(n_tiles), block(BLOCK_THREADS);
+    if (variant == 0) hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, block, 0, stream, descs, n_desc, raw);
+    else if (variant == 1) hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, block, 0, stream, descs, n_desc, raw);
+    else hipLaunchKernelGGL((materialize_elem<CONV>), grid, block, 0, stream, descs, n_desc, raw);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return FST_OK;
+}
+
+}  // namespace
+
+int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
+                         const void *raw_dev, int64_t src_bias, void *stream)
+{
+    if (n_desc == 0 || n_tiles == 0) return FST_OK;
+    uint32_t conv, variant;
+    if (cls < CONV_COUNT * 2) { conv = cls / 2; variant = cls % 2; }
+    else { conv = cls - CONV_COUNT * 2; variant = 2; }
+    const uint8_t *raw = static_cast<const uint8_t *>(raw_dev) + src_bias;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (conv) {
+    case CONV_COPY: return launch_conv<CONV_COPY>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_H2B: return launch_conv<CONV_H2B>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_B2H: return launch_conv<CONV_B2H>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_H2F: return launch_conv<CONV_H2F>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_B2F: return launch_conv<CONV_B2F>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_F2H: return launch_conv<CONV_F2H>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_F2B: return launch_conv<CONV_F2B>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    default: return fail(FST_E_ARG, "unknown launch class %u", cls);
+    }
+}
+
+}  // namespace fst

@@ -1,0 +1,169 @@
+// Host side of fst_materialize: checks the operands against what the kernels assume, builds the
+// device table of pieces for one group (or all), copies it into the caller's workspace and
+// launches one kernel per launch class (paper Section III-B: preprocessing offloaded to the GPU).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <mutex>
+#include <new>
+
+#include "fst_internal.h"
+
+namespace fst {
+
+namespace {
+
+uint32_t tiles_of(const Piece &pc)
+{
+    const uint64_t per = pc.path == PATH_VEC ? VEC_TILE_UNITS : ELEM_TILE_UNITS;
+    return uint32_t((pc.n_units + per - 1) / per);
+}
+
+}  // namespace
+
+// Builds the device image for groups [g0, g1) as ONE launch set (pieces of all those groups
+// merged per class).  slot = true: sources are addressed for the slot layout of group g0 (g1 must
+// be g0+1); the returned bias turns resident offsets into slot offsets.
+int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
+                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges, int64_t &bias)
+{
+    std::vector<const Piece *> order;
+    for (size_t g = g0; g < g1; ++g)
+        for (const Piece &pc : p->groups[g].pieces) order.push_back(&pc);
+    std::stable_sort(order.begin(), order.end(),
+                     [](const Piece *a, const Piece *b) { return launch_class(*a) < launch_class(*b); });
+    bias = 0;
+    if (slot) {
+        const Group &g = p->groups[g0];
+        // resident offset of file byte lo is raw_base + lo; in the slot it sits at lo % 256
+        bias = int64_t(g.lo % FST_RAW_ALIGN) - int64_t(p->raw_base[g.file] + g.lo);
+    }
+    image.clear();
+    ranges.clear();
+    image.reserve(order.size());
+    for (const Piece *pc : order) {
+        const Output &o = p->outputs[pc->output];
+        const uintptr_t out = reinterpret_cast<uintptr_t>(out_ptrs[pc->output]);
+        if (out == 0) return fail(FST_E_ARG, "out_ptrs[%u] is NULL but the output has %llu bytes", pc->output,
+                                  (unsigned long long)o.info.nbytes);
+        if (out % FST_OUTPUT_ALIGN)
+            return fail(FST_E_ALIGN, "out_ptrs[%u] is not %d-byte aligned", pc->output, FST_OUTPUT_ALIGN);
+        const uint64_t src_off = p->raw_base[o.info.file] + pc->src_file_off;
+        const int64_t eff = int64_t(src_off) + bias;
+        // the kernels read whole dwords around unaligned bytes: round the end up to 4
+        const uint64_t end = (uint64_t(eff) + pc->src_span + 3) & ~uint64_t(3);
+        if (eff < 0 || end > ((uint64_t(src_len) + 3) & ~uint64_t(3)))
+            return fail(FST_E_RANGE, "output %u reads bytes [%lld, %llu) but the buffer has %zu", pc->output,
+                        (long long)eff, (unsigned long long)(uint64_t(eff) + pc->src_span), src_len);
+        const uint32_t cls = launch_class(*pc);
+        if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(image.size()), 0, 0});
+        LaunchRange &r = ranges.back();
+        DevDesc d{};
+        d.src_off = src_off;
+        d.src_stride = pc->src_stride;
+        d.dst = uint64_t(out) + pc->dst_off;
+        d.n_units = pc->n_units;
+        d.units_per_row = pc->units_per_row;
+        d.tile0 = r.tiles;
+        d.n_tiles = tiles_of(*pc);
+        if (uint64_t(r.tiles) + d.n_tiles > 0x7FFFFFFFull) return fail(FST_E_RANGE, "too many tiles in one launch");
+        r.tiles += d.n_tiles;
+        r.count += 1;
+        image.push_back(d);
+    }
+    return FST_OK;
+}
+
+int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev,
+                  int64_t bias, void *stream)
+{
+    for (const LaunchRange &r : ranges)
+        if (int rc = launch_class_kernels(r.cls, table_dev + r.first, r.count, r.tiles, src_dev, bias, stream)) return rc;
+    return FST_OK;
+}
+
+namespace {
+
+// Host copies of the tables that in-flight uploads read from: one per (plan, group).  They live
+// until the process ends or the same group of the same plan is materialized again.
+struct UploadCache {
+    std::mutex mu;
+    std::vector<std::pair<std::pair<const fst_plan *, size_t>, std::vector<DevDesc>>> slots;
+    std::vector<DevDesc> &get(const fst_plan *p, size_t g)
+    {
+        for (auto &s : slots)
+            if (s.first.first == p && s.first.second == g) return s.second;
+        if (slots.size() >= 4096) slots.erase(slots.begin(), slots.begin() + 2048);
+        slots.emplace_back(std::make_pair(p, g), std::vector<DevDesc>());
+        return slots.back().second;
+    }
+};
+
+int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
+                     void *ws, size_t ws_len, void *stream, bool slot)
+{
+    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
+    size_t g0, g1;
+    if (group == FST_ALL_GROUPS) {
+        if (slot) return fail(FST_E_ARG, "fst_materialize_slot takes one group");
+        g0 = 0;
+        g1 = p->groups.size();
+    } else {
+        if (group >= p->groups.size()) return fail(FST_E_RANGE, "group %zu out of range", group);
+        g0 = group;
+        g1 = group + 1;
+    }
+    size_t n_pieces = 0;
+    for (size_t g = g0; g < g1; ++g) n_pieces += p->groups[g].pieces.size();
+    if (n_pieces == 0) return FST_OK;
+    if (!src_dev) return fail(FST_E_ARG, "fst_materialize: raw buffer is NULL");
+    if (reinterpret_cast<uintptr_t>(src_dev) % FST_RAW_ALIGN)
+        return fail(FST_E_ALIGN, "raw buffer is not %d-byte aligned", FST_RAW_ALIGN);
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
+    if (ws_len < n_pieces * sizeof(DevDesc))
+        return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, n_pieces * sizeof(DevDesc));
+
+    static UploadCache cache;
+    std::lock_guard<std::mutex> lock(cache.mu);
+    std::vector<DevDesc> &image = cache.get(p, group);
+    std::vector<LaunchRange> ranges;
+    int64_t bias = 0;
+    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image, ranges, bias)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(ws, image.data(), image.size() * sizeof(DevDesc), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail(FST_E_HIP, "table upload failed: %s", hipGetErrorString(e));
+    return launch_ranges(ranges, static_cast<const DevDesc *>(ws), src_dev, bias, stream);
+}
+
+}  // namespace
+}  // namespace fst
+
+using namespace fst;
+
+extern "C" {
+
+int fst_materialize(const void *raw_dev, size_t raw_len, const fst_plan *p, size_t group, void *const *out_ptrs,
+                    void *dev_workspace, size_t workspace_len, void *stream)
+{
+    try {
+        return materialize_impl(raw_dev, raw_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, false);
+    } catch (const std::bad_alloc &) {
+        return fail(FST_E_NOMEM, "out of memory");
+    } catch (...) {
+        return fail(FST_E_ARG, "unexpected internal error");
+    }
+}
+
+int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *p, size_t group,
+                         void *const *out_ptrs, void *dev_workspace, size_t workspace_len, void *stream)
+{
+    try {
+        return materialize_impl(slot_dev, slot_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, true);
+    } catch (const std::bad_alloc &) {
+        return fail(FST_E_NOMEM, "out of memory");
+    } catch (...) {
+        return fail(FST_E_ARG, "unexpected internal error");
+    }
+}
+
+}  // extern "C"

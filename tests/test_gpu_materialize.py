@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit
+(paper Section III-B: alignment fix, type conversion and partition on the GPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2505_23072_amd import binding as B
+from paper_2505_23072_amd import device
+from synth import writer
+from util_cases import FLOATS, make_file, random_bits, random_request
+from util_gpu import (first_diff, headers_of, materialize_resident, materialize_slots, oracle_outputs,
+                      upload_resident)
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(got, want, names, reqs, tag=""):
+    for i, (g, w) in enumerate(zip(got, want)):
+        assert g == w, f"{tag} output {i} {names[i]} {reqs[i]}: {first_diff(g, w)}"
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_files(seed):
+    rng = np.random.default_rng(1000 + seed)
+    world = int(rng.choice([1, 2, 4, 8]))
+    rank = int(rng.integers(world))
+    blobs, names, reqs = [], [], []
+    for f in range(int(rng.integers(1, 4))):
+        blob, ts = make_file(rng, n_tensors=8, big=True, prefix=f"f{f}.")
+        blobs.append(blob)
+        names += [n for n, _, _ in ts]
+        reqs += [random_request(rng, d, s, world) for _, d, s in ts]
+    print(f"seed {seed} world {world} rank {rank} files {[len(b) for b in blobs]}", flush=True)
+    want = oracle_outputs(blobs, names, reqs, rank, world)
+    got, plan = materialize_resident(blobs, names, reqs, rank, world)
+    _check(got, want, names, reqs, "all-groups")
+    got, _ = materialize_resident(blobs, names, reqs, rank, world, max_group_bytes=8192, per_group=True)
+    _check(got, want, names, reqs, "per-group")
+    got, _ = materialize_slots(blobs, names, reqs, rank, world, 16384)
+    _check(got, want, names, reqs, "slots")
+
+
+# several tiles (a tile is 64 KiB of output) and a ragged tail
+SHAPE = (523, 264)
+
+
+@pytest.mark.parametrize("residue", range(16))
+def test_every_source_alignment(residue):
+    """Body start at every residue mod 16, with an odd-sized tensor in front to shift the rest by one."""
+    rng = np.random.default_rng(residue)
+    ts = [("pad", "U8", (residue % 3,), random_bits(rng, "U8", (residue % 3,)).tobytes())]
+    for dt in ("BF16", "F16", "F32", "I8", "I64"):
+        ts.append((f"w.{dt}", dt, SHAPE, random_bits(rng, dt, SHAPE).tobytes()))
+        ts.append((f"v.{dt}", dt, (1031,), random_bits(rng, dt, (1031,)).tobytes()))
+    blob = writer.write_file(None, ts, None, residue)
+    names, reqs = [], []
+    for n, dt, shape, _ in ts[1:]:
+        dsts = [None] + ([d for d in FLOATS if d != dt] if dt in FLOATS else [])
+        for dst in dsts:
+            for dim, blocks in ((-1, 1), (0, 1), (1, 1)) if len(shape) == 2 else ((-1, 1),):
+                names.append(n)
+                reqs.append((dst, dim, blocks))
+    print(f"residue {residue}: {len(names)} requests", flush=True)
+    # world 1 for the vectors, a real split for the matrices
+    for world, rank in ((1, 0),):
+        want = oracle_outputs([blob], names, reqs, rank, world)
+        got, _ = materialize_resident([blob], names, reqs, rank, world)
+        _check(got, want, names, reqs, f"world {world}")
+    mats = [(n, r) for n, r in zip(names, reqs) if n.startswith("w.")]
+    mn, mr = [n for n, _ in mats], [r for _, r in mats]
+    # 523 rows do not split; use the 264 columns (dim 1) for world 8/3 and a blocked dim 0 elsewhere
+    mr1 = [(dst, 1, 1) for dst, _, _ in mr]
+    for world, rank in ((8, 5), (3, 1)):
+        want = oracle_outputs([blob], mn, mr1, rank, world)
+        got, _ = materialize_resident([blob], mn, mr1, rank, world)
+        _check(got, want, mn, mr1, f"world {world}")
+
+
+def test_blocked_and_ragged_rows():
+    """Fused-QKV style blocked split, rows whose byte length is not a multiple of 16, 3-D and 4-D."""
+    rng = np.random.default_rng(77)
+    ts = [("odd", "I8", (5,), random_bits(rng, "I8", (5,)).tobytes()),
+          ("qkv", "BF16", (3 * 8 * 40, 72), random_bits(rng, "BF16", (960, 72)).tobytes()),
+          ("qkv_b", "F16", (960,), random_bits(rng, "F16", (960,)).tobytes()),
+          ("ragged", "BF16", (64, 37), random_bits(rng, "BF16", (64, 37)).tobytes()),
+          ("ragged8", "I8", (40, 63), random_bits(rng, "I8", (40, 63)).tobytes()),
+          ("t3", "F32", (6, 16, 24), random_bits(rng, "F32", (6, 16, 24)).tobytes()),
+          ("t4", "F16", (2, 3, 8, 40), random_bits(rng, "F16", (2, 3, 8, 40)).tobytes())]
+    blob = writer.write_file(None, ts, None, 7)
+    for world in (1, 2, 4, 8):
+        names = ["qkv", "qkv", "qkv_b", "qkv_b", "t3", "t3", "t3", "t4", "t4", "t4", "odd"]
+        reqs = [(None, 0, 3), ("F16", 0, 3), (None, 0, 3), ("F32", 0, 3), ("BF16", 1, 1), (None, 2, 1),
+                ("F16", 0, 1) if 6 % world == 0 else ("F16", -1, 1),
+                (None, 2, 1), ("BF16", 3, 1), ("F32", 2, 1), (None, -1, 1)]
+        if world == 1:
+            names += ["ragged", "ragged8"]
+            reqs += [("F32", 1, 1), (None, 1, 1)]
+        for rank in sorted({0, world - 1}):
+            print(f"world {world} rank {rank}", flush=True)
+            want = oracle_outputs([blob], names, reqs, rank, world)
+            got, _ = materialize_resident([blob], names, reqs, rank, world)
+            _check(got, want, names, reqs, f"world {world} rank {rank}")
+    # rows of 37 two-byte / 63 one-byte elements split by a world that divides them: row pieces of
+    # 2, 9 and 7 bytes, none a multiple of 16
+    for world, rank, name, req in ((37, 11, "ragged", (None, 1, 1)), (37, 36, "ragged", ("F32", 1, 1)),
+                                   (7, 3, "ragged8", (None, 1, 1)), (9, 8, "ragged8", (None, 1, 1)),
+                                   (8, 3, "ragged8", (None, 0, 1))):
+        want = oracle_outputs([blob], [name], [req], rank, world)
+        got, _ = materialize_resident([blob], [name], [req], rank, world)
+        _check(got, want, [name], [req], f"ragged world {world}")
+
+
+@pytest.mark.parametrize("src,dst", [("F16", "BF16"), ("BF16", "F16"), ("F16", "F32"), ("BF16", "F32")])
+def test_exhaustive_16bit_conversions_on_device(src, dst):
+    """All 65536 source patterns, NaN payloads and subnormals included, at an odd source offset too."""
+    allbits = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    for lead in (0, 1, 2):
+        ts = [("lead", "U8", (lead,), bytes(lead)), ("x", src, (1 << 16,), allbits.tobytes())]
+        blob = writer.write_file(None, ts, None, 0)
+        got, _ = materialize_resident([blob], ["x"], [(dst, -1, 1)])
+        want = orc.cast_array(allbits, src, dst).tobytes()
+        assert got[0] == want, f"{src}->{dst} lead {lead}: {first_diff(got[0], want)}"
+
+
+@pytest.mark.parametrize("dst", ["BF16", "F16"])
+def test_f32_conversions_on_device(dst):
+    rng = np.random.default_rng(5)
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    parts = [hi | lo for lo in (0x0000, 0x7FFF, 0x8000, 0x8001, 0xFFFF, 0x0001)]
+    hi13 = np.arange(1 << 19, dtype=np.uint32) << 13
+    parts += [hi13 | lo for lo in (0x0000, 0x0FFF, 0x1000, 0x1001, 0x1FFF)]
+    sub = np.uint32(0x33000000) + np.arange(0, 0x05800000, 0x3FF, dtype=np.uint32)
+    parts += [sub, sub | np.uint32(0x80000000), rng.integers(0, 1 << 32, 2_000_000, dtype=np.uint64).astype(np.uint32)]
+    x = np.concatenate(parts)
+    for lead in (0, 3):
+        blob = writer.write_file(None, [("lead", "U8", (lead,), bytes(lead)), ("x", "F32", (len(x),), x.tobytes())], None, 0)
+        got, _ = materialize_resident([blob], ["x"], [(dst, -1, 1)])
+        want = orc.cast_array(x, "F32", dst).tobytes()
+        assert got[0] == want, f"F32->{dst} lead {lead}: {first_diff(got[0], want)}"
+
+
+def test_on_a_side_stream_and_empty_plan():
+    rng = np.random.default_rng(3)
+    blob, ts = make_file(rng, n_tensors=6, big=True)
+    names = [n for n, _, _ in ts]
+    reqs = [(None, -1, 1)] * len(names)
+    s = torch.cuda.Stream()
+    got, plan = materialize_resident([blob], names, reqs, stream=s)
+    _check(got, oracle_outputs([blob], names, reqs), names, reqs, "side stream")
+    # a plan whose outputs are all empty launches nothing
+    e = writer.write_file(None, [("e", "F32", (0, 4), b""), ("f", "F16", (3, 0), b"")])
+    got, plan = materialize_resident([e], ["e", "f"], [(None, -1, 1), ("F32", -1, 1)])
+    assert got == [b"", b""] and plan.group_count() == 0
+
+
+def test_operand_checks_reject_before_any_launch():
+    rng = np.random.default_rng(4)
+    blob, ts = make_file(rng, n_tensors=4, big=True)
+    names = [n for n, _, shape in ts if int(np.prod(shape)) > 0]
+    reqs = [(None, -1, 1)] * len(names)
+    hs = headers_of([blob])
+    raw, bases, raw_len = upload_resident([blob])
+    plan = B.Plan(hs, bases, names, reqs)
+    bufs, ptrs = device.alloc_outputs(plan)
+    ws = device.device_bytes(plan.workspace_bytes())
+
+    def err(**kw):
+        a = dict(raw_ptr=raw.data_ptr(), raw_len=raw_len, group=B.FST_ALL_GROUPS, out_ptrs=ptrs,
+                 workspace_ptr=ws.data_ptr(), workspace_len=ws.numel())
+        a.update(kw)
+        with pytest.raises(B.FstError) as e:
+            B.fst_materialize(a["raw_ptr"], a["raw_len"], plan, a["group"], a["out_ptrs"], a["workspace_ptr"],
+                              a["workspace_len"], 0)
+        return e.value.name
+
+    assert err(raw_ptr=raw.data_ptr() + 16) == "FST_E_ALIGN"
+    assert err(out_ptrs=[ptrs[0] + 64] + ptrs[1:]) == "FST_E_ALIGN"
+    assert err(out_ptrs=[0] + ptrs[1:]) == "FST_E_ARG"
+    assert err(raw_len=len(blob) // 2) == "FST_E_RANGE"
+    assert err(workspace_len=32) == "FST_E_RANGE"
+    assert err(workspace_ptr=ws.data_ptr() + 8) == "FST_E_ALIGN"
+    assert err(group=plan.group_count()) == "FST_E_RANGE"
+    with pytest.raises(B.FstError):
+        B.fst_materialize_slot(raw.data_ptr(), raw_len, plan, B.FST_ALL_GROUPS, ptrs, ws.data_ptr(), ws.numel(), 0)
+    torch.cuda.synchronize()

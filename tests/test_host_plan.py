@@ -1,0 +1,178 @@
+"""The load planner (host code, no GPU).  The copy descriptors it exports are interpreted here with
+numpy slicing (plus the oracle's element conversion) and must reproduce the oracle's result; groups must
+cover each output exactly once and respect the size limit (paper Section III-A/B)."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2505_23072_amd import binding as B
+from util_cases import ES, make_file, random_request
+
+
+def _headers(blobs):
+    hs = []
+    for b in blobs:
+        n = B.fst_header_len(b[:8])
+        hs.append(B.Header(b[:8 + n], len(b)))
+    return hs
+
+
+def _interpret(plan, blobs):
+    """Run the public descriptors on the CPU: returns one bytes object per output."""
+    outs = [np.zeros(plan.output(i)["nbytes"], np.uint8) for i in range(plan.output_count())]
+    written = [np.zeros(len(o), np.uint8) for o in outs]
+    for k in range(plan.descriptor_count()):
+        d = plan.descriptor(k)
+        g = plan.group(d["group"])
+        assert g["file"] == d["file"]
+        src = np.frombuffer(blobs[d["file"]], np.uint8)
+        es_s, es_d = ES[d["src_dtype"]], ES[d["dst_dtype"]]
+        rb_s, rb_d = d["row_elems"] * es_s, d["row_elems"] * es_d
+        for r in range(d["n_rows"]):
+            lo = d["src_file_off"] + r * d["src_stride"]
+            assert g["lo"] <= lo and lo + rb_s <= g["hi"], "descriptor reads outside its group"
+            row = src[lo:lo + rb_s]
+            if d["src_dtype"] != d["dst_dtype"]:
+                row = orc.cast_array(row, d["src_dtype"], d["dst_dtype"]).view(np.uint8)
+            at = d["dst_off"] + r * rb_d
+            outs[d["output"]][at:at + rb_d] = row
+            written[d["output"]][at:at + rb_d] += 1
+    for w in written:
+        assert np.all(w == 1), "an output byte is written zero or several times"
+    return [o.tobytes() for o in outs]
+
+
+def _oracle_outputs(blobs, names, reqs, rank, world):
+    tabs = [orc.parse(b, len(b)) for b in blobs]
+    res = []
+    for nm, (dst, dim, blocks) in zip(names, reqs):
+        for b, tab in zip(blobs, tabs):
+            try:
+                t = tab.find(nm)
+            except orc.OracleError:
+                continue
+            stored = np.frombuffer(b, np.uint8, t.end - t.begin, tab.body_off + t.begin)
+            out, shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, rank, world)
+            res.append((out.tobytes(), shape, dst or t.dtype))
+            break
+    return res
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_descriptors_reproduce_the_oracle(seed):
+    rng = np.random.default_rng(seed)
+    world = int(rng.choice([1, 2, 3, 4, 8]))
+    rank = int(rng.integers(world))
+    nfiles = int(rng.integers(1, 4))
+    blobs, names, reqs = [], [], []
+    for f in range(nfiles):
+        blob, ts = make_file(rng, n_tensors=7, big=(seed % 2 == 0), prefix=f"f{f}.")
+        blobs.append(blob)
+        names += [n for n, _, _ in ts]
+        reqs += [random_request(rng, d, s, world) for _, d, s in ts]
+    hs = _headers(blobs)
+    bases = [4096 * 256 * i for i in range(nfiles)]
+    plan = B.Plan(hs, bases, names, reqs, rank, world)
+    want = _oracle_outputs(blobs, names, reqs, rank, world)
+    for max_bytes in (0, 4096, 20000, 1 << 20):
+        ng = plan.set_groups(max_bytes)
+        assert ng == plan.group_count()
+        got = _interpret(plan, blobs)
+        for i, (w, shape, dt) in enumerate(want):
+            info = plan.output(i)
+            assert info["shape"] == shape and info["dtype"] == dt and info["nbytes"] == len(w)
+            assert got[i] == w, (names[i], reqs[i], max_bytes)
+        rd = wr = 0
+        for g in range(ng):
+            gi = plan.group(g)
+            assert gi["hi"] > gi["lo"] and gi["slot_phase"] == gi["lo"] % 256
+            assert gi["slot_bytes"] == gi["slot_phase"] + gi["hi"] - gi["lo"]
+            if max_bytes:
+                assert gi["slot_bytes"] <= max_bytes
+            rd += gi["read_bytes"]
+            wr += gi["write_bytes"]
+        assert wr == plan.write_bytes() == sum(len(w) for w, _, _ in want)
+        assert rd == plan.read_bytes()
+    assert plan.workspace_bytes() % 256 == 0
+
+
+def test_plan_geometry_of_named_cases():
+    """Closed-form checks of rows / strides for the partitions the paper's workloads use."""
+    from synth import writer
+    w = np.arange(64 * 48, dtype=np.uint16)
+    qkv = np.arange(96 * 16, dtype=np.uint16)
+    blob = writer.write_file(None, [("w", "BF16", (64, 48), w.tobytes()), ("qkv", "BF16", (96, 16), qkv.tobytes()),
+                                    ("b", "BF16", (96,), qkv[:96].tobytes())], None, 3)
+    h = _headers([blob])
+    body = h[0].body_offset()
+    plan = B.Plan(h, [0], ["w", "w", "qkv", "b", "w"],
+                  [(None, 0, 1), (None, 1, 1), (None, 0, 3), ("F32", 0, 3), (None, 1, 1)], rank=2, world=4)
+    d = [plan.descriptor(i) for i in range(plan.descriptor_count())]
+    by_out = {x["output"]: x for x in d}
+    # dim 0: one contiguous run of 16 rows starting at row 32
+    assert (by_out[0]["n_rows"], by_out[0]["row_elems"], by_out[0]["src_file_off"]) == (1, 16 * 48, body + 32 * 48 * 2)
+    # dim 1: 64 rows of 12 elements, stride one stored row, starting at column 24
+    assert (by_out[1]["n_rows"], by_out[1]["row_elems"], by_out[1]["src_stride"], by_out[1]["src_file_off"]) == \
+           (64, 12, 96, body + 24 * 2)
+    # blocked: 3 rows of 8*16 elements, stride one block (32 rows)
+    q0 = body + 64 * 48 * 2
+    assert (by_out[2]["n_rows"], by_out[2]["row_elems"], by_out[2]["src_stride"], by_out[2]["src_file_off"]) == \
+           (3, 8 * 16, 32 * 16 * 2, q0 + 16 * 16 * 2)
+    assert plan.output(2)["shape"] == (24, 16) and plan.output(3)["shape"] == (24,)
+    assert plan.output(3)["dtype"] == "F32" and plan.output(3)["nbytes"] == 96
+    assert plan.read_bytes() == 2 * (16 * 48 + 64 * 12 + 24 * 16 + 24 + 64 * 12)
+    assert plan.write_bytes() == 2 * (16 * 48 + 64 * 12 + 24 * 16 + 64 * 12) + 4 * 24
+    # world 1 collapses a dim-1 request to one contiguous row
+    p1 = B.Plan(h, [0], ["w"], [(None, 1, 1)], 0, 1)
+    assert p1.descriptor(0)["n_rows"] == 1 and p1.descriptor(0)["row_elems"] == 64 * 48
+
+
+def test_plan_errors():
+    from synth import writer
+    a = np.zeros(24, np.uint16).tobytes()
+    f0 = writer.write_file(None, [("x", "F16", (4, 6), a), ("i", "I16", (24,), a)])
+    f1 = writer.write_file(None, [("y", "F16", (4, 6), a)])
+    dup = writer.write_file(None, [("x", "F16", (24,), a)])
+    h0, h1, hd = _headers([f0, f1, dup])
+
+    def err(headers, bases, names, reqs, rank=0, world=2):
+        with pytest.raises(B.FstError) as e:
+            B.Plan(headers, bases, names, reqs, rank, world)
+        return e.value.name
+
+    assert err([h0, h1], [0, 4096], ["z"], [(None, -1, 1)]) == "FST_E_NOT_FOUND"
+    assert err([h0, hd], [0, 4096], ["x"], [(None, -1, 1)]) == "FST_E_DUP_NAME"
+    assert err([h0], [100], ["x"], [(None, -1, 1)]) == "FST_E_ALIGN"
+    assert err([h0], [0], ["x"], [(None, 2, 1)]) == "FST_E_SHARD"
+    assert err([h0], [0], ["i"], [(None, 1, 1)]) == "FST_E_SHARD"            # dim 1 of a vector
+    assert err([h0], [0], ["x"], [(None, 1, 1)], world=4) == "FST_E_SHARD"   # 6 % 4
+    assert err([h0], [0], ["x"], [(None, 0, 3)]) == "FST_E_SHARD"            # 4 % 6
+    assert err([h0], [0], ["x"], [(None, 1, 2)]) == "FST_E_SHARD"            # blocks need dim 0
+    assert err([h0], [0], ["x"], [(None, -1, 2)]) == "FST_E_SHARD"
+    assert err([h0], [0], ["x"], [(None, 0, 0)]) == "FST_E_SHARD"
+    assert err([h0], [0], ["x"], [(None, 0, 1)], rank=2, world=2) == "FST_E_SHARD"
+    assert err([h0], [0], ["x"], [(None, 0, 1)], rank=0, world=0) == "FST_E_SHARD"
+    assert err([h0], [0], ["i"], [("F16", -1, 1)]) == "FST_E_CAST"
+    assert err([h0], [0], ["x"], [("F64", -1, 1)]) == "FST_E_CAST"
+    p = B.Plan([h0, h1], [0, 4096], ["x", "y", "i"], [("BF16", 0, 1), (None, 1, 1), (None, -1, 1)], 1, 2)
+    with pytest.raises(B.FstError) as e:
+        p.set_groups(100)
+    assert e.value.name == "FST_E_ARG"
+    assert p.group_count() == 2            # still usable: one group per file
+    with pytest.raises(B.FstError):
+        p.output(3)
+    with pytest.raises(B.FstError):
+        p.group(2)
+    with pytest.raises(B.FstError):
+        p.descriptor(99)
+
+
+def test_uniform_plan_matches_per_name_requests():
+    from synth import writer
+    a = np.arange(32 * 8, dtype=np.uint16)
+    blob = writer.write_file(None, [("p", "F16", (32, 8), a.tobytes()), ("q", "F16", (16, 8), a[:128].tobytes())])
+    h = _headers([blob])
+    u = B.Plan.uniform(h, [0], ["p", "q"], "BF16", 0, rank=1, world=2)
+    e = B.Plan(h, [0], ["p", "q"], [("BF16", 0, 1)] * 2, 1, 2)
+    assert [u.descriptor(i) for i in range(2)] == [e.descriptor(i) for i in range(2)]
+    assert [u.output(i) for i in range(2)] == [e.output(i) for i in range(2)]
