@@ -101,7 +101,10 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
     };
     (void)base_abs;
 
-    if (rows == 1) {
+    if (rows == 1 && dst0 % 16) {
+        // a cut inside an output with ragged rows: the vector path needs 16-byte aligned stores
+        if (int rc = push(PATH_ELEM, src0, dst0, row_units, row_units, 1)) return rc;
+    } else if (rows == 1) {
         const uint64_t full = row_units / chunk, tail = row_units % chunk;
         if (full) {
             // one long row: present it as rows of one tile each so that in-row offsets stay 32-bit
