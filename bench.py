@@ -102,7 +102,7 @@ def main() -> int:
                                          ws.numel(), flags)
 
         e2e = {}
-        st = stage(0)      # also leaves the raw buffer resident for the timed steps below
+        stage(B.FST_STAGE_NO_KERNELS)      # leaves the raw bytes resident for the timed steps below
         if not args.no_e2e:
             def best(flags):
                 ts = []
@@ -133,7 +133,6 @@ def main() -> int:
                 "source": "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread",
             }
             log("e2e", e2e)
-            stage(0)
         for fd in fds:
             os.close(fd)
         stager.close()

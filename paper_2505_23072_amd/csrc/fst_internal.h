@@ -98,11 +98,18 @@ inline uint32_t launch_class(const Piece &p)
 }
 
 // Geometry of the kernels, fixed at compile time and needed by the planner to count tiles.
-constexpr uint32_t BLOCK_THREADS = 256;
+// The vector kernels run 1024-thread workgroups (16 wavefronts) in which every lane moves
+// VEC_UNROLL chunks: one tile = 4096 chunks = 64 KiB of 16-byte chunks.
+constexpr uint32_t VEC_BLOCK_THREADS = 1024;
 constexpr uint32_t VEC_UNROLL = 4;                       // chunks in flight per thread
-constexpr uint32_t VEC_ITERS = 4;                        // unrolled batches per tile
-constexpr uint32_t VEC_TILE_UNITS = BLOCK_THREADS * VEC_UNROLL * VEC_ITERS;   // chunks per tile
-constexpr uint32_t ELEM_TILE_UNITS = BLOCK_THREADS * 16;                      // elements per tile
+constexpr uint32_t VEC_TILE_UNITS = VEC_BLOCK_THREADS * VEC_UNROLL;           // chunks per tile
+constexpr uint32_t ELEM_BLOCK_THREADS = 256;
+constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 // elements per tile
+// Workgroups are dealt to the 8 XCDs round-robin.  The tile index is permuted so that each XCD
+// works on runs of XCD_RUN consecutive tiles (1 MiB of output), which measured faster than both
+// tile-by-tile interleaving and giving each XCD one contiguous eighth.
+constexpr uint32_t XCD_COUNT = 8;
+constexpr uint32_t XCD_RUN = 16;
 
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
 uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)

@@ -2,7 +2,7 @@
 // Section III-B: alignment fix and type conversion done in one pass on the GPU; one rank's
 // partition is taken in the same pass).  Pure data movement: HBM-bound, no matrix cores.
 //
-// Work is a table of pieces (DevDesc).  One workgroup of 256 threads = 4 wavefronts takes one
+// Work is a table of pieces (DevDesc).  One workgroup of 1024 threads = 16 wavefronts takes one
 // tile of a piece; the piece is found by a binary search over the table's tile prefix, done with
 // scalar loads since it only depends on the workgroup index.  In the vector path a lane moves one
 // chunk at a time: 16 source bytes when nothing is converted, 8 elements otherwise, always
@@ -31,13 +31,19 @@ __device__ __forceinline__ u32x4 gload16(const void *p)
 {
     return *(const FST_GLOBAL u32x4_a4 *)(p);
 }
+// The raw bytes are read once and the outputs are not read back: streaming (non-temporal)
+// accesses keep them from displacing each other in the caches.
+__device__ __forceinline__ u32x4 gload16_stream(const void *p)
+{
+    return __builtin_nontemporal_load((const FST_GLOBAL u32x4_a4 *)(p));
+}
 __device__ __forceinline__ uint32_t gload4(const void *p)
 {
     return *(const FST_GLOBAL uint32_t *)(p);
 }
 __device__ __forceinline__ void gstore16(void *p, u32x4 v)
 {
-    *(FST_GLOBAL u32x4 *)(p) = v;
+    __builtin_nontemporal_store(v, (FST_GLOBAL u32x4 *)(p));
 }
 
 struct Chunk32 { u32x4 lo, hi; };                        // up to 32 source or result bytes
@@ -51,7 +57,7 @@ __device__ __forceinline__ uint32_t shift_bytes(uint32_t hi, uint32_t lo, uint32
 template <bool BYTE>
 __device__ __forceinline__ u32x4 load16(const uint8_t *src)
 {
-    if (!BYTE) return gload16(src);
+    if (!BYTE) return gload16_stream(src);
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
     const uint32_t sh = uint32_t(a) & 3u;
     const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
@@ -70,8 +76,8 @@ __device__ __forceinline__ Chunk32 load32(const uint8_t *src)
 {
     Chunk32 c;
     if (!BYTE) {
-        c.lo = gload16(src);
-        c.hi = gload16(src + 16);
+        c.lo = gload16_stream(src);
+        c.hi = gload16_stream(src + 16);
         return c;
     }
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
@@ -217,46 +223,55 @@ __device__ __forceinline__ void vec_tile(const uint8_t *src, uint8_t *dst, uint3
                                          uint64_t stride)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
-    for (uint32_t base = 0; base < (FULL ? VEC_TILE_UNITS : n); base += BLOCK_THREADS * VEC_UNROLL) {
-        Chunk32 v[VEC_UNROLL];
+    Chunk32 v[VEC_UNROLL];
 #pragma unroll
-        for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
-            const uint32_t i = base + u * BLOCK_THREADS + threadIdx.x;
-            if (FULL || i < n) {
-                const uint8_t *s;
-                if (upr == 0) {
-                    s = src + uint64_t(i) * CS;
-                } else {
-                    const uint32_t cc = col0 + i;                        // chunk index from the row start
-                    const uint32_t r = cc / upr;
-                    s = src + uint64_t(r) * stride + uint64_t(cc - r * upr) * CS;
-                }
-                if (CS == 16) v[u].lo = load16<BYTE>(s); else v[u] = load32<BYTE>(s);
+    for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
+        const uint32_t i = u * VEC_BLOCK_THREADS + threadIdx.x;
+        if (FULL || i < n) {
+            const uint8_t *s;
+            if (upr == 0) {
+                s = src + uint64_t(i) * CS;
+            } else {
+                const uint32_t cc = col0 + i;                        // chunk index from the row start
+                const uint32_t r = cc / upr;
+                s = src + uint64_t(r) * stride + uint64_t(cc - r * upr) * CS;
             }
+            if (CS == 16) v[u].lo = load16<BYTE>(s); else v[u] = load32<BYTE>(s);
         }
+    }
 #pragma unroll
-        for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
-            const uint32_t i = base + u * BLOCK_THREADS + threadIdx.x;
-            if (FULL || i < n) {
-                const Chunk32 o = convert_chunk<CONV>(v[u]);
-                uint8_t *t = dst + uint64_t(i) * CD;
-                gstore16(t, o.lo);
-                if (CD == 32) gstore16(t + 16, o.hi);
-            }
+    for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
+        const uint32_t i = u * VEC_BLOCK_THREADS + threadIdx.x;
+        if (FULL || i < n) {
+            const Chunk32 o = convert_chunk<CONV>(v[u]);
+            uint8_t *t = dst + uint64_t(i) * CD;
+            gstore16(t, o.lo);
+            if (CD == 32) gstore16(t + 16, o.hi);
         }
     }
 }
 
+// Workgroup index -> tile index.  Workgroup i runs on XCD i % 8; within every span of 8*XCD_RUN
+// workgroups, XCD x gets the tiles x*XCD_RUN .. x*XCD_RUN+XCD_RUN-1 of the span, in order.
+__device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_wg)
+{
+    constexpr uint32_t SPAN = XCD_COUNT * XCD_RUN;
+    if (wg >= n_wg / SPAN * SPAN) return wg;             // the ragged last span keeps its order
+    const uint32_t r = wg % SPAN;
+    return wg - r + (r % XCD_COUNT) * XCD_RUN + r / XCD_COUNT;
+}
+
 template <uint32_t CONV, bool BYTE>
-__global__ __launch_bounds__(BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs, uint32_t n_desc,
-                                                                 const uint8_t *__restrict__ raw)
+__global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs, uint32_t n_desc,
+                                                                     const uint8_t *__restrict__ raw)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
-    const uint32_t b = blockIdx.x;
+    const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
     const DevDesc *d = descs + find_piece(descs, n_desc, b);
-    const uint64_t c0 = uint64_t(b - d->tile0) * VEC_TILE_UNITS;        // first chunk of this tile
-    const uint64_t left = d->n_units - c0;
-    const uint32_t n = left < VEC_TILE_UNITS ? uint32_t(left) : VEC_TILE_UNITS;
+    const uint32_t t = b - d->tile0;                                    // tile inside the piece
+    const uint64_t c0 = uint64_t(t) * VEC_TILE_UNITS;                   // first chunk of this tile
+    // only a piece's last tile can be short; decided on 32-bit tile counts
+    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units - c0) : VEC_TILE_UNITS;
     const uint32_t upr = d->units_per_row;
     const uint64_t stride = d->src_stride;
     uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + c0 * CD;
@@ -279,22 +294,22 @@ __global__ __launch_bounds__(BLOCK_THREADS) void materialize_vec(const DevDesc *
 // Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
 // byte when nothing is converted) per thread and step; sources are read bytewise.
 template <uint32_t CONV>
-__global__ __launch_bounds__(BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs, uint32_t n_desc,
+__global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs, uint32_t n_desc,
                                                                   const uint8_t *__restrict__ raw)
 {
     constexpr uint32_t ES = CONV == CONV_COPY ? 1 : (CONV == CONV_F2H || CONV == CONV_F2B) ? 4 : 2;
     constexpr uint32_t ED = CONV == CONV_COPY ? 1 : (CONV == CONV_H2F || CONV == CONV_B2F) ? 4 : 2;
     const uint32_t b = blockIdx.x;
     const DevDesc *d = descs + find_piece(descs, n_desc, b);
-    const uint64_t e0 = uint64_t(b - d->tile0) * ELEM_TILE_UNITS;
-    const uint64_t left = d->n_units - e0;
-    const uint32_t n = left < ELEM_TILE_UNITS ? uint32_t(left) : ELEM_TILE_UNITS;
+    const uint32_t t = b - d->tile0;
+    const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
+    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units - e0) : ELEM_TILE_UNITS;
     const uint32_t upr = d->units_per_row;
     const uint64_t row0 = e0 / upr;
     const uint32_t col0 = uint32_t(e0 - row0 * upr);
     const uint8_t *src = raw + d->src_off + row0 * d->src_stride;
     uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + e0 * ED;
-    for (uint32_t i = threadIdx.x; i < n; i += BLOCK_THREADS) {
+    for (uint32_t i = threadIdx.x; i < n; i += ELEM_BLOCK_THREADS) {
         const uint64_t cc = uint64_t(col0) + i;
         const uint64_t r = cc / upr;
         const uint8_t *s = src + r * d->src_stride + (cc - r * upr) * ES;
@@ -313,10 +328,13 @@ template <uint32_t CONV>
 int launch_conv(uint32_t variant, const DevDesc *descs, uint32_t n_desc, uint32_t n_tiles, const uint8_t *raw,
                 hipStream_t stream)
 {
-    const dim3 grid(n_tiles), block(BLOCK_THREADS);
-    if (variant == 0) hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, block, 0, stream, descs, n_desc, raw);
-    else if (variant == 1) hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, block, 0, stream, descs, n_desc, raw);
-    else hipLaunchKernelGGL((materialize_elem<CONV>), grid, block, 0, stream, descs, n_desc, raw);
+    const dim3 grid(n_tiles);
+    if (variant == 0)
+        hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
+    else if (variant == 1)
+        hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
+    else
+        hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return FST_OK;
