@@ -1,0 +1,136 @@
+"""Full-size parity on the five configurations (synthetic stand-ins for the paper's Table I models:
+same tensor names, shapes, dtypes and file splits; values N(0, 0.02) from a seeded pool).  The
+procedural source produces the file bytes on the fly for the staging ring, and again, independently,
+for the oracle, one sampled tensor at a time.  Every comparison is bit-exact."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2505_23072_amd import binding as B
+from paper_2505_23072_amd import device
+from synth import specs
+from synth.source import ProceduralModel
+from util_gpu import first_diff
+
+pytestmark = pytest.mark.gpu
+
+GB = 1 << 30
+
+
+def _plan(model, spec, bases):
+    hs = [B.Header(h, s) for h, s in zip(model.headers, model.sizes)]
+    names = [t.name for f in spec.files for t in f.tensors]
+    reqs = [(t.dst_dtype, t.shard_dim, t.blocks) for f in spec.files for t in f.tensors]
+    return B.Plan(hs, bases, names, reqs, spec.rank, spec.world), names, reqs
+
+
+def _check_sample(model, spec, plan, bufs, names, reqs, picks, threads=16):
+    """Oracle over the picked outputs (batched on plain threads), compared with the device results."""
+    tabs = [orc.parse(h, s) for h, s in zip(model.headers, model.sizes)]
+    jobs, meta = [], []
+    for i in picks:
+        info = plan.output(i)
+        fi = info["file"]
+        t = tabs[fi].find(names[i])
+        stored = model.read(fi, tabs[fi].body_off + t.begin, t.end - t.begin)
+        dst, dim, blocks = reqs[i]
+        shape, nb = orc.result_info(t.dtype, t.shape, dst, dim, blocks, spec.rank, spec.world)
+        assert shape == info["shape"] and nb == info["nbytes"] and (dst or t.dtype) == info["dtype"], names[i]
+        jobs.append(dict(stored=stored, dtype=t.dtype, shape=t.shape, dst_dtype=dst, shard_dim=dim, blocks=blocks,
+                         rank=spec.rank, world=spec.world, out=np.empty(nb, np.uint8)))
+        meta.append(i)
+    orc.materialize_jobs(jobs, threads)
+    for i, j in zip(meta, jobs):
+        got = bufs[i][:j["out"].nbytes].cpu().numpy()
+        assert got.tobytes() == j["out"].tobytes(), f"{names[i]} {reqs[i]}: {first_diff(got.tobytes(), j['out'].tobytes())}"
+
+
+def _picks(spec, names, layers):
+    """Non-layer tensors plus every tensor of the given layers."""
+    keep = []
+    for i, n in enumerate(names):
+        parts = n.split(".")
+        idx = [int(p) for p in parts if p.isdigit()]
+        if not idx or idx[0] in layers:
+            keep.append(i)
+    return keep
+
+
+def _run_resident(spec, layers, group_bytes=GB):
+    t0 = time.time()
+    model = ProceduralModel(spec)
+    bases, raw_len = device.file_bases(model.sizes)
+    plan, names, reqs = _plan(model, spec, bases)
+    plan.set_groups(group_bytes)
+    raw = device.device_bytes(raw_len)
+    ws = device.device_bytes(plan.workspace_bytes())
+    bufs, ptrs = device.alloc_outputs(plan)
+    st = B.Stager(16, 12, 32 << 20)
+    try:
+        stats = st.stage_resident(plan, model.read_fn, model.ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(), ws.numel())
+    finally:
+        st.close()
+    print(f"{spec.name}: staged {stats['staged_bytes'] / 1e9:.2f} GB in {stats['seconds_total']:.2f}s "
+          f"({plan.group_count()} groups), setup {time.time() - t0:.1f}s", flush=True)
+    assert plan.write_bytes() == sum(plan.output(i)["nbytes"] for i in range(plan.output_count()))
+    _check_sample(model, spec, plan, bufs, names, reqs, _picks(spec, names, layers))
+    # the launch configuration the benchmark times: one call for everything, raw bytes resident
+    for b in bufs:
+        b.zero_()
+    B.fst_materialize(raw.data_ptr(), raw_len, plan, B.FST_ALL_GROUPS, ptrs, ws.data_ptr(), ws.numel(), 0)
+    torch.cuda.synchronize()
+    _check_sample(model, spec, plan, bufs, names, reqs, _picks(spec, names, layers[:1]))
+    return plan
+
+
+def _run_streamed(spec, layers, dev_slots, slot_bytes):
+    t0 = time.time()
+    model = ProceduralModel(spec)
+    plan, names, reqs = _plan(model, spec, [0] * len(model.sizes))
+    ng = plan.set_groups(slot_bytes)
+    slots = [device.device_bytes(slot_bytes) for _ in range(dev_slots)]
+    ws = device.device_bytes(plan.workspace_bytes())
+    bufs, ptrs = device.alloc_outputs(plan)
+    st = B.Stager(16, 14, 32 << 20)
+    try:
+        stats = st.stage_streamed(plan, model.read_fn, model.ctx, [s.data_ptr() for s in slots], slot_bytes, ptrs,
+                                  ws.data_ptr(), ws.numel())
+    finally:
+        st.close()
+    print(f"{spec.name}: streamed {stats['staged_bytes'] / 1e9:.2f} GB in {stats['seconds_total']:.2f}s through "
+          f"{dev_slots}x{slot_bytes / GB:.1f} GiB device slots ({ng} groups), outputs {plan.write_bytes() / 1e9:.2f} GB, "
+          f"setup {time.time() - t0:.1f}s", flush=True)
+    _check_sample(model, spec, plan, bufs, names, reqs, _picks(spec, names, layers))
+    return plan
+
+
+def test_config2_llama7b_resident():
+    spec = specs.config2_llama7b()
+    plan = _run_resident(spec, layers=[0, 23, 24, 31])
+    assert plan.output_count() == 291 and plan.read_bytes() == plan.write_bytes() == 13_476_831_232
+
+
+def test_config3_llama13b_fp16_to_bf16():
+    spec = specs.config3_llama13b()
+    plan = _run_resident(spec, layers=[0, 13, 39])
+    assert plan.output_count() == 363 and plan.read_bytes() == plan.write_bytes() == 26_031_728_640
+    assert plan.output(5)["dtype"] == "BF16"
+
+
+def test_config4_llama70b_tp8_rank0_streamed():
+    spec = specs.config4_llama70b()
+    plan = _run_streamed(spec, layers=[0, 41, 79], dev_slots=3, slot_bytes=4 * GB)
+    assert plan.output_count() == 723
+    assert plan.write_bytes() == 18_163_974_144 == plan.read_bytes()
+
+
+def test_config5_bloom176b_tp8_rank0_streamed():
+    spec = specs.config5_bloom176b()
+    plan = _run_streamed(spec, layers=[0, 35, 69], dev_slots=3, slot_bytes=4 * GB)
+    assert plan.output_count() == 845
+    assert plan.write_bytes() == 50_374_675_456
+    # layer norms are widened to fp32: they read 2 bytes and write 4 per element
+    assert plan.write_bytes() - plan.read_bytes() == 16_285_696 // 2

@@ -1,0 +1,170 @@
+"""GPU tests of the staging ring (paper Section III-A: pinned bounce buffer + host-to-device copies)
+together with the kernels: tiny ring slots force every wrap and split case; results must equal the
+oracle's and the staged bytes must equal the file bytes."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_23072_amd import binding as B
+from paper_2505_23072_amd import device
+from synth import specs
+from synth.source import ProceduralModel
+from util_cases import make_file, random_request
+from util_gpu import first_diff, headers_of, oracle_outputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, tmp_path, nfiles=3):
+    rng = np.random.default_rng(seed)
+    world = int(rng.choice([1, 2, 4]))
+    rank = int(rng.integers(world))
+    blobs, names, reqs, paths = [], [], [], []
+    for f in range(nfiles):
+        blob, ts = make_file(rng, n_tensors=8, big=True, prefix=f"f{f}.")
+        p = str(tmp_path / f"f{f}.safetensors")
+        open(p, "wb").write(blob)
+        blobs.append(blob)
+        paths.append(p)
+        names += [n for n, _, _ in ts]
+        reqs += [random_request(rng, d, s, world) for _, d, s in ts]
+    return blobs, paths, names, reqs, rank, world
+
+
+class Fds:
+    def __init__(self, paths):
+        self.fds = [os.open(p, os.O_RDONLY) for p in paths]
+        self.arr = (ctypes.c_int * len(self.fds))(*self.fds)
+
+    @property
+    def ctx(self):
+        return ctypes.addressof(self.arr)
+
+    def close(self):
+        for fd in self.fds:
+            os.close(fd)
+
+
+@pytest.mark.parametrize("seed,slots,threads,slot_bytes,group_bytes", [
+    (0, 3, 4, 4096, 16384), (1, 2, 1, 4096, 4096), (2, 8, 8, 65536, 1 << 20), (3, 1, 3, 8192, 0), (4, 5, 2, 4096, 50000)])
+def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, tmp_path):
+    blobs, paths, names, reqs, rank, world = _case(seed, tmp_path)
+    print(f"seed {seed} ring {slots}x{slot_bytes} threads {threads} groups {group_bytes}", flush=True)
+    want = oracle_outputs(blobs, names, reqs, rank, world)
+    hs = headers_of(blobs)
+    bases, raw_len = device.file_bases([len(b) for b in blobs])
+    plan = B.Plan(hs, bases, names, reqs, rank, world)
+    plan.set_groups(group_bytes)
+    raw = device.device_bytes(raw_len)
+    raw.fill_(0xCC)
+    ws = device.device_bytes(plan.workspace_bytes())
+    bufs, ptrs = device.alloc_outputs(plan)
+    st = B.Stager(slots, threads, slot_bytes)
+    fds = Fds(paths)
+    try:
+        stats = st.stage_resident(plan, B.read_fds_fn(), fds.ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(), ws.numel())
+        staged = sum(plan.group(g)["hi"] - plan.group(g)["lo"] for g in range(plan.group_count()))
+        assert stats["staged_bytes"] == staged and stats["n_copies"] >= plan.group_count()
+        host = raw.cpu().numpy()
+        for g in range(plan.group_count()):                     # staged bytes == file bytes
+            gi = plan.group(g)
+            at = bases[gi["file"]]
+            assert host[at + gi["lo"]:at + gi["hi"]].tobytes() == blobs[gi["file"]][gi["lo"]:gi["hi"]]
+        for i, w in enumerate(want):
+            got = bufs[i][:len(w)].cpu().numpy().tobytes() if len(w) else b""
+            assert got == w, f"{names[i]} {reqs[i]}: {first_diff(got, w)}"
+        # copy-only modes run the same ring without kernels / without reads
+        for flags in (B.FST_STAGE_NO_KERNELS, B.FST_STAGE_NO_KERNELS | B.FST_STAGE_NO_READ):
+            s2 = st.stage_resident(plan, B.read_fds_fn(), fds.ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(),
+                                   ws.numel(), flags)
+            assert s2["staged_bytes"] == staged
+    finally:
+        fds.close()
+        st.close()
+
+
+@pytest.mark.parametrize("seed,dev_slots,group_bytes", [(10, 2, 32768), (11, 1, 8192), (12, 3, 100000), (13, 4, 4096)])
+def test_streamed_ring(seed, dev_slots, group_bytes, tmp_path):
+    """Raw buffer = ring of device slots smaller than the files: groups are cut to fit."""
+    blobs, paths, names, reqs, rank, world = _case(seed, tmp_path)
+    print(f"seed {seed} device slots {dev_slots}x{group_bytes}", flush=True)
+    want = oracle_outputs(blobs, names, reqs, rank, world)
+    hs = headers_of(blobs)
+    plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
+    ng = plan.set_groups(group_bytes)
+    assert ng > len(blobs)
+    slots = [device.device_bytes(group_bytes) for _ in range(dev_slots)]
+    ws = device.device_bytes(plan.workspace_bytes())
+    bufs, ptrs = device.alloc_outputs(plan)
+    st = B.Stager(4, 3, 4096)
+    fds = Fds(paths)
+    try:
+        st.stage_streamed(plan, B.read_fds_fn(), fds.ctx, [s.data_ptr() for s in slots], group_bytes, ptrs,
+                          ws.data_ptr(), ws.numel())
+        for i, w in enumerate(want):
+            got = bufs[i][:len(w)].cpu().numpy().tobytes() if len(w) else b""
+            assert got == w, f"{names[i]} {reqs[i]}: {first_diff(got, w)}"
+        with pytest.raises(B.FstError) as e:      # slots smaller than a group are refused up front
+            st.stage_streamed(plan, B.read_fds_fn(), fds.ctx, [s.data_ptr() for s in slots], group_bytes // 2, ptrs,
+                              ws.data_ptr(), ws.numel())
+        assert e.value.name == "FST_E_RANGE"
+    finally:
+        fds.close()
+        st.close()
+
+
+def test_read_failure_is_reported(tmp_path):
+    blobs, paths, names, reqs, rank, world = _case(20, tmp_path, nfiles=1)
+    short = str(tmp_path / "short.safetensors")
+    open(short, "wb").write(blobs[0][:len(blobs[0]) // 2])       # the file ends before its header says
+    hs = headers_of(blobs)
+    plan = B.Plan(hs, [0], names, reqs, rank, world)
+    plan.set_groups(8192)
+    raw = device.device_bytes(len(blobs[0]) + 256)
+    ws = device.device_bytes(plan.workspace_bytes())
+    bufs, ptrs = device.alloc_outputs(plan)
+    st = B.Stager(2, 2, 4096)
+    fds = Fds([short])
+    try:
+        with pytest.raises(B.FstError) as e:
+            st.stage_resident(plan, B.read_fds_fn(), fds.ctx, raw.data_ptr(), raw.numel(), ptrs, ws.data_ptr(), ws.numel())
+        assert e.value.name == "FST_E_IO"
+        with pytest.raises(B.FstError) as e:      # raw buffer too small for the plan
+            st.stage_resident(plan, B.read_fds_fn(), fds.ctx, raw.data_ptr(), 1024, ptrs, ws.data_ptr(), ws.numel())
+        assert e.value.name == "FST_E_RANGE"
+        torch.cuda.synchronize()
+    finally:
+        fds.close()
+        st.close()
+
+
+def test_tiny_checkpoint_end_to_end(tmp_path):
+    """The tiny configuration (2-layer Llama-like model plus int8[37] and bool[13] tensors that push the
+    weights to odd offsets): files -> tensors, every tensor against the oracle."""
+    from oracle import oracle as orc
+    spec = specs.config1_tiny()
+    model = ProceduralModel(spec)
+    paths = model.write_all(str(tmp_path))
+    blob = open(paths[0], "rb").read()
+    table = orc.parse(blob, len(blob))
+    offs = {t.name: (table.body_off + t.begin) % 16 for t in table.tensors}
+    assert offs["model.embed_tokens.weight"] % 2 == (table.body_off + 37) % 2     # odd shift from int8[37]
+    out = device.load_files(paths, group_bytes=1 << 20)
+    assert len(out) == spec.n_tensors == 23
+    for t in table.tensors:
+        stored = np.frombuffer(blob, np.uint8, t.end - t.begin, table.body_off + t.begin)
+        want, shape = orc.materialize(stored, t.dtype, t.shape)
+        got = out[t.name]
+        assert tuple(got.shape) == shape and got.dtype == device.TORCH_DTYPE[t.dtype]
+        gb = got.contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes()
+        assert gb == want.tobytes(), f"{t.name}: {first_diff(gb, want.tobytes())}"
+    # norm weights are ones, as the configuration says
+    assert torch.all(out["model.norm.weight"].float() == 1.0)
+
+
+def test_smoke_entry_point():
+    import __graft_entry__
+    __graft_entry__.smoke()
