@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-baseline budget per leg")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 4 GiB device copy kernel (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
     ap.add_argument("--slots", type=int, default=16)
     ap.add_argument("--slot-bytes", type=int, default=32 << 20)
@@ -136,6 +138,16 @@ def main() -> int:
         for fd in fds:
             os.close(fd)
         stager.close()
+
+        if args.calibrate_copy:
+            # a plain copy of known size: 4 GiB read + 4 GiB written per dispatch
+            n_cal = 1 << 30
+            a = torch.empty(n_cal, dtype=torch.int32, device=dev).fill_(7)
+            b = torch.empty(n_cal, dtype=torch.int32, device=dev)
+            for _ in range(3):
+                torch.add(a, 0, out=b)          # one elementwise kernel: reads a, writes b
+            torch.cuda.synchronize()
+            del a, b
 
         # ---------------- timed steps: raw bytes resident in HBM
         stream = torch.cuda.Stream()

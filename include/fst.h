@@ -174,23 +174,43 @@ int fst_plan_output(const fst_plan *p, size_t i, fst_output_info *out);
  * means one group per file.  Invalidates earlier group indices.
  *
  * Resident layout: byte o of file f is at raw + raw_base[f] + o.
- * Slot layout: the group's bytes are alone in a slot; byte o of the file is at
- *   slot + slot_phase + (o - lo), with slot_phase = lo % FST_RAW_ALIGN, so every source keeps the
- *   alignment it has in the file; the slot must hold slot_bytes = slot_phase + hi - lo bytes.
+ * Slot layout: the group's staged bytes are alone in a slot.  A group stages one or more extents
+ *   (byte ranges of its file); byte o of extent e is at slot + e.slot_offset + (o - e.lo), where
+ *   e.slot_offset % FST_RAW_ALIGN == e.lo % FST_RAW_ALIGN, so every source keeps the alignment it has
+ *   in the file; the slot must hold slot_bytes.
+ *
+ * fst_plan_set_groups stages, per group, everything from its first to its last needed byte as one
+ * extent (whole files when every tensor is requested: Section III-A).  fst_plan_set_groups_sparse
+ * additionally leaves out file ranges that no requested piece reads when they are longer than
+ * min_gap_bytes -- the other ranks' shares of dim-0 partitions, unrequested tensors.  Section
+ * III-B warns that selecting each rank's ranges degrades into many small scattered reads: a large
+ * min_gap_bytes (megabytes) keeps every extent large.  In the resident layout the skipped ranges
+ * of the raw buffer are simply never written nor read.
  */
 int fst_plan_set_groups(fst_plan *p, uint64_t max_group_bytes, size_t *n_groups);
+int fst_plan_set_groups_sparse(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes,
+                               size_t *n_groups);
 
 typedef struct fst_group_info {
     uint32_t file;
     uint32_t n_descriptors;
-    uint64_t lo, hi;                 /* file byte range that must be present */
-    uint64_t slot_phase, slot_bytes;
+    uint32_t n_extents;
+    uint32_t reserved;
+    uint64_t lo, hi;                 /* first staged file byte, last staged file byte + 1 */
+    uint64_t slot_bytes;             /* slot layout: bytes of slot the group needs */
+    uint64_t staged_bytes;           /* sum of the extents' lengths */
     uint64_t read_bytes;             /* source bytes the kernels read for this group */
     uint64_t write_bytes;            /* output bytes they write */
 } fst_group_info;
 
+typedef struct fst_extent {
+    uint64_t lo, hi;                 /* file byte range that must be present */
+    uint64_t slot_offset;            /* slot layout: where byte lo sits in the slot */
+} fst_extent;
+
 size_t fst_plan_group_count(const fst_plan *p);
 int fst_plan_group(const fst_plan *p, size_t g, fst_group_info *out);
+int fst_plan_group_extent(const fst_plan *p, size_t g, size_t i, fst_extent *out);
 
 /*
  * Copy descriptors, exposed for inspection and tests.  One descriptor copies n_rows rows of
@@ -224,7 +244,9 @@ void fst_plan_free(fst_plan *p);
  * synchronised.  out_ptrs (host array of output_count device pointers): out_ptrs[i] receives
  * output i, must be FST_OUTPUT_ALIGN-aligned (FST_E_ALIGN) and hold nbytes; outputs of zero bytes
  * may be NULL.  dev_workspace (device): workspace_len >= fst_plan_workspace_bytes, 256-aligned;
- * each call overwrites it, so calls in flight at once need separate workspaces.
+ * each call overwrites it, so calls in flight on different streams need separate workspaces.
+ * The plan keeps the host copy of the uploaded table: keep the plan alive, and do not re-cut its
+ * groups, until the stream has passed this call.
  *
  * fst_materialize: resident layout; raw_dev (device, FST_RAW_ALIGN-aligned) must cover every
  * byte the group reads (FST_E_RANGE if raw_len is too small) and be readable up to the next
@@ -274,8 +296,8 @@ int fst_read_fds(void *ctx, int32_t file, uint64_t off, void *dst, uint64_t len)
                                      (measures the pure host-to-device time) */
 
 /*
- * Resident load: stage every group's bytes [lo,hi) to raw_dev + raw_base[file] + lo and
- * materialize group after group.  Blocks until all work has finished on the device.
+ * Resident load: stage every group's extents to raw_dev + raw_base[file] + lo and materialize
+ * group after group.  Blocks until all work has finished on the device.
  */
 int fst_stage_resident(fst_stager *s, const fst_plan *p, fst_read_fn read, void *read_ctx,
                        void *raw_dev, size_t raw_len, void *const *out_ptrs,
@@ -287,7 +309,7 @@ int fst_stage_resident(fst_stager *s, const fst_plan *p, fst_read_fn read, void 
  * n_dev_slots device slots of dev_slot_bytes each (slot_dev[i], FST_RAW_ALIGN-aligned); group g
  * goes to slot g % n_dev_slots in slot layout and the slot is reused once the kernels of its
  * previous group have finished.  Every group must fit (FST_E_RANGE): cut the plan with
- * fst_plan_set_groups first.  dev_workspace must hold n_dev_slots * fst_plan_workspace_bytes.
+ * fst_plan_set_groups first.  dev_workspace must hold fst_plan_workspace_bytes.
  */
 int fst_stage_streamed(fst_stager *s, const fst_plan *p, fst_read_fn read, void *read_ctx,
                        void *const *slot_dev, size_t n_dev_slots, size_t dev_slot_bytes,

@@ -42,9 +42,13 @@ class fst_output_info(Structure):
 
 
 class fst_group_info(Structure):
-    _fields_ = [("file", c_uint32), ("n_descriptors", c_uint32), ("lo", c_uint64), ("hi", c_uint64),
-                ("slot_phase", c_uint64), ("slot_bytes", c_uint64), ("read_bytes", c_uint64),
-                ("write_bytes", c_uint64)]
+    _fields_ = [("file", c_uint32), ("n_descriptors", c_uint32), ("n_extents", c_uint32), ("reserved", c_uint32),
+                ("lo", c_uint64), ("hi", c_uint64), ("slot_bytes", c_uint64), ("staged_bytes", c_uint64),
+                ("read_bytes", c_uint64), ("write_bytes", c_uint64)]
+
+
+class fst_extent(Structure):
+    _fields_ = [("lo", c_uint64), ("hi", c_uint64), ("slot_offset", c_uint64)]
 
 
 class fst_descriptor(Structure):
@@ -87,6 +91,8 @@ _SIGNATURES = {
     "fst_plan_output_count": (c_size_t, [c_void_p]),
     "fst_plan_output": (c_int, [c_void_p, c_size_t, POINTER(fst_output_info)]),
     "fst_plan_set_groups": (c_int, [c_void_p, c_uint64, POINTER(c_size_t)]),
+    "fst_plan_set_groups_sparse": (c_int, [c_void_p, c_uint64, c_uint64, POINTER(c_size_t)]),
+    "fst_plan_group_extent": (c_int, [c_void_p, c_size_t, c_size_t, POINTER(fst_extent)]),
     "fst_plan_group_count": (c_size_t, [c_void_p]),
     "fst_plan_group": (c_int, [c_void_p, c_size_t, POINTER(fst_group_info)]),
     "fst_plan_descriptor_count": (c_size_t, [c_void_p]),
@@ -252,9 +258,13 @@ class Plan:
         return dict(dtype=DTYPE_NAMES[oi.dtype], shape=tuple(oi.shape[d] for d in range(oi.ndim)),
                     nbytes=oi.nbytes, align=oi.align, file=oi.file)
 
-    def set_groups(self, max_group_bytes: int) -> int:
+    def set_groups(self, max_group_bytes: int, min_gap_bytes: Optional[int] = None) -> int:
+        """min_gap_bytes given: do not stage unread file ranges longer than that."""
         n = c_size_t()
-        _check(lib().fst_plan_set_groups(self._p, max_group_bytes, byref(n)))
+        if min_gap_bytes is None:
+            _check(lib().fst_plan_set_groups(self._p, max_group_bytes, byref(n)))
+        else:
+            _check(lib().fst_plan_set_groups_sparse(self._p, max_group_bytes, min_gap_bytes, byref(n)))
         return n.value
 
     def group_count(self) -> int:
@@ -263,7 +273,13 @@ class Plan:
     def group(self, g: int) -> dict:
         gi = fst_group_info()
         _check(lib().fst_plan_group(self._p, g, byref(gi)))
-        return {k: getattr(gi, k) for k, _ in fst_group_info._fields_}
+        out = {k: getattr(gi, k) for k, _ in fst_group_info._fields_}
+        out["extents"] = []
+        for i in range(gi.n_extents):
+            e = fst_extent()
+            _check(lib().fst_plan_group_extent(self._p, g, i, byref(e)))
+            out["extents"].append((e.lo, e.hi, e.slot_offset))
+        return out
 
     def descriptor_count(self) -> int:
         return lib().fst_plan_descriptor_count(self._p)

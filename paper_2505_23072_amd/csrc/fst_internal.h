@@ -3,6 +3,8 @@
 
 #include <cstdarg>
 #include <cstdint>
+#include <map>
+#include <mutex>
 #include <string>
 #include <unordered_map>
 #include <utility>
@@ -44,7 +46,7 @@ enum Conv : uint32_t { CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CO
 
 // One unit of kernel work, as uploaded to the device (64 bytes).
 struct DevDesc {
-    uint64_t src_off;        // byte offset of row 0, relative to the resident raw buffer
+    uint64_t src_off;        // byte offset of row 0 from the source pointer of the launch
     uint64_t src_stride;     // bytes between rows
     uint64_t dst;            // device address of the first output byte of this piece
     uint64_t n_units;        // VEC: chunks in total (rows * units_per_row); ELEM: elements
@@ -71,9 +73,14 @@ struct Piece {
     uint64_t read_bytes = 0, write_bytes = 0;
 };
 
+// A byte range of a file that is staged; in the slot layout its first byte sits at slot_off.
+struct Extent { uint64_t lo = 0, hi = 0, slot_off = 0; };
+
 struct Group {
     uint32_t file = 0;
-    uint64_t lo = 0, hi = 0;
+    uint64_t lo = 0, hi = 0;                // first and last+1 staged file byte
+    std::vector<Extent> extents;            // ascending, disjoint
+    uint64_t slot_bytes = 0;                // slot space the extents take
     size_t desc_begin = 0, desc_end = 0;    // public descriptors [begin, end)
     std::vector<Piece> pieces;              // sorted by launch class
     uint64_t read_bytes = 0, write_bytes = 0;
@@ -126,22 +133,28 @@ struct fst_plan {
     std::vector<fst_descriptor> descs;        // public view, grouped
     std::vector<fst::Group> groups;
     uint64_t read_bytes = 0, write_bytes = 0;
+    uint64_t min_gap = UINT64_MAX;            // unread file ranges longer than this are not staged
     size_t max_group_pieces = 0;
     size_t total_pieces = 0;
+    // Host copies of the device tables that fst_materialize uploads, one per group index (and one
+    // for "all groups").  They belong to the plan so that an enqueued upload never outlives its
+    // source; re-cutting the groups drops them.
+    mutable std::mutex image_mu;
+    mutable std::map<size_t, std::vector<fst::DevDesc>> images;
 };
 
 namespace fst {
-int build_groups(fst_plan *p, uint64_t max_group_bytes);
+int build_groups(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes);
 
 // One kernel launch: pieces [first, first+count) of a device table, all of one launch class.
 struct LaunchRange { uint32_t cls, first, count, tiles; };
 // Device table for groups [g0, g1) merged into one launch set.  slot: address sources for the
-// slot layout of group g0 (then g1 == g0+1); bias is what to add to the source pointer.
+// slot layout of group g0 (then g1 == g0+1) instead of the resident layout.
 int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
-                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges, int64_t &bias);
+                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges);
 int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev,
-                  int64_t bias, void *stream);
+                  void *stream);
 // Launch the kernels of one class.  descs_dev: the class's DevDesc array on the device.
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
-                         const void *raw_dev, int64_t src_bias, void *stream);
+                         const void *raw_dev, void *stream);
 }  // namespace fst

@@ -343,13 +343,13 @@ int launch_conv(uint32_t variant, const DevDesc *descs, uint32_t n_desc, uint32_
 }  // namespace
 
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
-                         const void *raw_dev, int64_t src_bias, void *stream)
+                         const void *raw_dev, void *stream)
 {
     if (n_desc == 0 || n_tiles == 0) return FST_OK;
     uint32_t conv, variant;
     if (cls < CONV_COUNT * 2) { conv = cls / 2; variant = cls % 2; }
     else { conv = cls - CONV_COUNT * 2; variant = 2; }
-    const uint8_t *raw = static_cast<const uint8_t *>(raw_dev) + src_bias;
+    const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (conv) {
     case CONV_COPY: return launch_conv<CONV_COPY>(variant, descs_dev, n_desc, n_tiles, raw, s);

@@ -23,21 +23,15 @@ uint32_t tiles_of(const Piece &pc)
 
 // Builds the device image for groups [g0, g1) as ONE launch set (pieces of all those groups
 // merged per class).  slot = true: sources are addressed for the slot layout of group g0 (g1 must
-// be g0+1); the returned bias turns resident offsets into slot offsets.
+// be g0+1): a piece's bytes are found through the extent that holds them.
 int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
-                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges, int64_t &bias)
+                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges)
 {
     std::vector<const Piece *> order;
     for (size_t g = g0; g < g1; ++g)
         for (const Piece &pc : p->groups[g].pieces) order.push_back(&pc);
     std::stable_sort(order.begin(), order.end(),
                      [](const Piece *a, const Piece *b) { return launch_class(*a) < launch_class(*b); });
-    bias = 0;
-    if (slot) {
-        const Group &g = p->groups[g0];
-        // resident offset of file byte lo is raw_base + lo; in the slot it sits at lo % 256
-        bias = int64_t(g.lo % FST_RAW_ALIGN) - int64_t(p->raw_base[g.file] + g.lo);
-    }
     image.clear();
     ranges.clear();
     image.reserve(order.size());
@@ -48,13 +42,24 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
                                   (unsigned long long)o.info.nbytes);
         if (out % FST_OUTPUT_ALIGN)
             return fail(FST_E_ALIGN, "out_ptrs[%u] is not %d-byte aligned", pc->output, FST_OUTPUT_ALIGN);
-        const uint64_t src_off = p->raw_base[o.info.file] + pc->src_file_off;
-        const int64_t eff = int64_t(src_off) + bias;
+        uint64_t src_off;
+        if (slot) {
+            // the extent with the largest lo <= the piece's first byte
+            const std::vector<Extent> &ex = p->groups[g0].extents;
+            auto it = std::upper_bound(ex.begin(), ex.end(), pc->src_file_off,
+                                       [](uint64_t v, const Extent &e) { return v < e.lo; });
+            if (it == ex.begin() || pc->src_file_off + pc->src_span > (it - 1)->hi)
+                return fail(FST_E_RANGE, "output %u: source bytes are not inside one staged extent", pc->output);
+            --it;
+            src_off = it->slot_off + (pc->src_file_off - it->lo);
+        } else {
+            src_off = p->raw_base[o.info.file] + pc->src_file_off;
+        }
         // the kernels read whole dwords around unaligned bytes: round the end up to 4
-        const uint64_t end = (uint64_t(eff) + pc->src_span + 3) & ~uint64_t(3);
-        if (eff < 0 || end > ((uint64_t(src_len) + 3) & ~uint64_t(3)))
-            return fail(FST_E_RANGE, "output %u reads bytes [%lld, %llu) but the buffer has %zu", pc->output,
-                        (long long)eff, (unsigned long long)(uint64_t(eff) + pc->src_span), src_len);
+        const uint64_t end = (src_off + pc->src_span + 3) & ~uint64_t(3);
+        if (end > ((uint64_t(src_len) + 3) & ~uint64_t(3)))
+            return fail(FST_E_RANGE, "output %u reads bytes [%llu, %llu) but the buffer has %zu", pc->output,
+                        (unsigned long long)src_off, (unsigned long long)(src_off + pc->src_span), src_len);
         const uint32_t cls = launch_class(*pc);
         if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(image.size()), 0, 0});
         LaunchRange &r = ranges.back();
@@ -74,30 +79,14 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
     return FST_OK;
 }
 
-int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev,
-                  int64_t bias, void *stream)
+int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev, void *stream)
 {
     for (const LaunchRange &r : ranges)
-        if (int rc = launch_class_kernels(r.cls, table_dev + r.first, r.count, r.tiles, src_dev, bias, stream)) return rc;
+        if (int rc = launch_class_kernels(r.cls, table_dev + r.first, r.count, r.tiles, src_dev, stream)) return rc;
     return FST_OK;
 }
 
 namespace {
-
-// Host copies of the tables that in-flight uploads read from: one per (plan, group).  They live
-// until the process ends or the same group of the same plan is materialized again.
-struct UploadCache {
-    std::mutex mu;
-    std::vector<std::pair<std::pair<const fst_plan *, size_t>, std::vector<DevDesc>>> slots;
-    std::vector<DevDesc> &get(const fst_plan *p, size_t g)
-    {
-        for (auto &s : slots)
-            if (s.first.first == p && s.first.second == g) return s.second;
-        if (slots.size() >= 4096) slots.erase(slots.begin(), slots.begin() + 2048);
-        slots.emplace_back(std::make_pair(p, g), std::vector<DevDesc>());
-        return slots.back().second;
-    }
-};
 
 int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
                      void *ws, size_t ws_len, void *stream, bool slot)
@@ -123,16 +112,14 @@ int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, siz
     if (ws_len < n_pieces * sizeof(DevDesc))
         return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, n_pieces * sizeof(DevDesc));
 
-    static UploadCache cache;
-    std::lock_guard<std::mutex> lock(cache.mu);
-    std::vector<DevDesc> &image = cache.get(p, group);
+    std::lock_guard<std::mutex> lock(p->image_mu);
+    std::vector<DevDesc> &image = p->images[group];
     std::vector<LaunchRange> ranges;
-    int64_t bias = 0;
-    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image, ranges, bias)) return rc;
+    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image, ranges)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipMemcpyAsync(ws, image.data(), image.size() * sizeof(DevDesc), hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail(FST_E_HIP, "table upload failed: %s", hipGetErrorString(e));
-    return launch_ranges(ranges, static_cast<const DevDesc *>(ws), src_dev, bias, stream);
+    return launch_ranges(ranges, static_cast<const DevDesc *>(ws), src_dev, stream);
 }
 
 }  // namespace

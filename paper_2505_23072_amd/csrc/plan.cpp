@@ -124,25 +124,67 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
     return FST_OK;
 }
 
+uint64_t round_up_256(uint64_t v) { return (v + FST_RAW_ALIGN - 1) / FST_RAW_ALIGN * FST_RAW_ALIGN; }
+
+// Slot space of an extent: it starts at its file phase (lo % 256) so sources keep their alignment,
+// and the next extent starts on the following 256-byte boundary.
+uint64_t extent_space(uint64_t lo, uint64_t hi) { return round_up_256(lo % FST_RAW_ALIGN + (hi - lo)); }
+
+// Slot space of the group if the byte range [s_lo, s_hi) were added (ranges arrive in file order).
+uint64_t space_with(const Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
+{
+    if (g.extents.empty()) return extent_space(s_lo, s_hi);
+    const Extent &last = g.extents.back();
+    if (s_lo <= last.hi || s_lo - last.hi <= min_gap)
+        return g.slot_bytes - extent_space(last.lo, last.hi) + extent_space(last.lo, std::max(last.hi, s_hi));
+    return g.slot_bytes + extent_space(s_lo, s_hi);
+}
+
+void add_range(Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
+{
+    g.slot_bytes = space_with(g, s_lo, s_hi, min_gap);
+    if (!g.extents.empty() && (s_lo <= g.extents.back().hi || s_lo - g.extents.back().hi <= min_gap)) {
+        g.extents.back().hi = std::max(g.extents.back().hi, s_hi);
+    } else {
+        Extent e;
+        e.lo = s_lo;
+        e.hi = s_hi;
+        g.extents.push_back(e);
+    }
+    g.lo = g.extents.front().lo;
+    g.hi = std::max(g.hi, s_hi);
+}
+
 void close_group(fst_plan *p, Group &g, size_t desc_begin)
 {
     g.desc_begin = desc_begin;
     g.desc_end = p->descs.size();
+    uint64_t at = 0;
+    for (Extent &e : g.extents) {
+        e.slot_off = at + e.lo % FST_RAW_ALIGN;
+        at += extent_space(e.lo, e.hi);
+    }
+    g.slot_bytes = at;
     std::stable_sort(g.pieces.begin(), g.pieces.end(),
                      [](const Piece &a, const Piece &b) { return launch_class(a) < launch_class(b); });
 }
 
 }  // namespace
 
-int build_groups(fst_plan *p, uint64_t max_bytes)
+int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap)
 {
     if (max_bytes != 0 && max_bytes < kMinGroupBytes)
         return fail(FST_E_ARG, "max_group_bytes must be 0 or at least %llu", (unsigned long long)kMinGroupBytes);
-    // 255 bytes of a slot may go to keeping the file's alignment phase
-    const uint64_t budget = max_bytes ? max_bytes - (FST_RAW_ALIGN - 1) : UINT64_MAX;
+    // in a slot an extent starts at its file phase (up to 255 bytes) and is padded to 256
+    const uint64_t budget = max_bytes ? max_bytes - 2 * (FST_RAW_ALIGN - 1) : UINT64_MAX;
+    {
+        std::lock_guard<std::mutex> lock(p->image_mu);
+        p->images.clear();
+    }
     p->descs.clear();
     p->groups.clear();
     p->read_bytes = p->write_bytes = 0;
+    p->min_gap = min_gap;
 
     // outputs per file, in file order
     std::vector<std::vector<uint32_t>> per_file(p->n_files);
@@ -159,11 +201,9 @@ int build_groups(fst_plan *p, uint64_t max_bytes)
         });
         bool open = false;
         size_t desc_begin = 0;
-        auto start = [&](uint64_t lo) {
+        auto start = [&]() {
             G.emplace_back();
             G.back().file = f;
-            G.back().lo = lo;
-            G.back().hi = lo;
             desc_begin = p->descs.size();
             open = true;
         };
@@ -178,11 +218,10 @@ int build_groups(fst_plan *p, uint64_t max_bytes)
             const uint64_t s_lo = o.src_file_off;
             const uint64_t s_hi = s_lo + (o.n_rows - 1) * o.src_stride + row_bytes;
             if (s_hi - s_lo <= budget) {
-                if (open && std::max(G.back().hi, s_hi) - G.back().lo > budget) finish();
-                if (!open) start(s_lo);
+                if (open && max_bytes && space_with(G.back(), s_lo, s_hi, min_gap) > max_bytes) finish();
+                if (!open) start();
                 Group &g = G.back();
-                g.lo = std::min(g.lo, s_lo);
-                g.hi = std::max(g.hi, s_hi);
+                add_range(g, s_lo, s_hi, min_gap);
                 if (int rc = add_work(p, g, oi, 0, o.n_rows, 0, 0)) return rc;
                 continue;
             }
@@ -192,8 +231,9 @@ int build_groups(fst_plan *p, uint64_t max_bytes)
                 const uint64_t rows_per = 1 + (budget - row_bytes) / o.src_stride;
                 for (uint64_t r = 0; r < o.n_rows; r += rows_per) {
                     const uint64_t r1 = std::min(o.n_rows, r + rows_per);
-                    start(s_lo + r * o.src_stride);
-                    G.back().hi = G.back().lo + (r1 - r - 1) * o.src_stride + row_bytes;
+                    start();
+                    const uint64_t c_lo = s_lo + r * o.src_stride;
+                    add_range(G.back(), c_lo, c_lo + (r1 - r - 1) * o.src_stride + row_bytes, min_gap);
                     if (int rc = add_work(p, G.back(), oi, r, r1, 0, 0)) return rc;
                     finish();
                 }
@@ -203,8 +243,9 @@ int build_groups(fst_plan *p, uint64_t max_bytes)
                 for (uint64_t r = 0; r < o.n_rows; ++r)
                     for (uint64_t e = 0; e < o.row_elems; e += cut) {
                         const uint64_t e1 = std::min(o.row_elems, e + cut);
-                        start(s_lo + r * o.src_stride + e * es_s);
-                        G.back().hi = G.back().lo + (e1 - e) * es_s;
+                        start();
+                        const uint64_t c_lo = s_lo + r * o.src_stride + e * es_s;
+                        add_range(G.back(), c_lo, c_lo + (e1 - e) * es_s, min_gap);
                         if (int rc = add_work(p, G.back(), oi, r, r, e, e1)) return rc;
                         finish();
                     }
@@ -314,7 +355,7 @@ int plan_impl(const fst_header *const *hdrs, const uint64_t *raw_base, size_t n_
         if (numel == 0) { o.n_rows = 0; o.row_elems = 0; }
         o.info.nbytes = numel * fst_dtype_size(dd);
     }
-    if (int rc = build_groups(p.get(), 0)) return rc;
+    if (int rc = build_groups(p.get(), 0, UINT64_MAX)) return rc;
     *out = p.release();
     return FST_OK;
 }
@@ -362,19 +403,24 @@ int fst_plan_output(const fst_plan *p, size_t i, fst_output_info *out)
     return FST_OK;
 }
 
-int fst_plan_set_groups(fst_plan *p, uint64_t max_group_bytes, size_t *n_groups)
+int fst_plan_set_groups_sparse(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes, size_t *n_groups)
 {
     if (!p) return fail(FST_E_ARG, "fst_plan_set_groups: plan is NULL");
     int rc;
-    try { rc = build_groups(p, max_group_bytes); }
+    try { rc = build_groups(p, max_group_bytes, min_gap_bytes); }
     catch (const std::bad_alloc &) { rc = fail(FST_E_NOMEM, "out of memory"); }
     catch (...) { rc = fail(FST_E_ARG, "unexpected internal error"); }
     if (rc) {                       // leave the plan usable: back to one group per file
-        try { build_groups(p, 0); } catch (...) {}
+        try { build_groups(p, 0, UINT64_MAX); } catch (...) {}
         return rc;
     }
     if (n_groups) *n_groups = p->groups.size();
     return FST_OK;
+}
+
+int fst_plan_set_groups(fst_plan *p, uint64_t max_group_bytes, size_t *n_groups)
+{
+    return fst_plan_set_groups_sparse(p, max_group_bytes, UINT64_MAX, n_groups);
 }
 
 size_t fst_plan_group_count(const fst_plan *p) { return p ? p->groups.size() : 0; }
@@ -386,12 +432,26 @@ int fst_plan_group(const fst_plan *p, size_t g, fst_group_info *out)
     const Group &gr = p->groups[g];
     out->file = gr.file;
     out->n_descriptors = uint32_t(gr.desc_end - gr.desc_begin);
+    out->n_extents = uint32_t(gr.extents.size());
     out->lo = gr.lo;
     out->hi = gr.hi;
-    out->slot_phase = gr.lo % FST_RAW_ALIGN;
-    out->slot_bytes = out->slot_phase + (gr.hi - gr.lo);
+    out->slot_bytes = gr.slot_bytes;
+    out->staged_bytes = 0;
+    for (const Extent &e : gr.extents) out->staged_bytes += e.hi - e.lo;
     out->read_bytes = gr.read_bytes;
     out->write_bytes = gr.write_bytes;
+    return FST_OK;
+}
+
+int fst_plan_group_extent(const fst_plan *p, size_t g, size_t i, fst_extent *out)
+{
+    if (!p || !out) return fail(FST_E_ARG, "fst_plan_group_extent: NULL argument");
+    if (g >= p->groups.size()) return fail(FST_E_RANGE, "group index %zu out of range", g);
+    if (i >= p->groups[g].extents.size()) return fail(FST_E_RANGE, "extent index %zu out of range", i);
+    const Extent &e = p->groups[g].extents[i];
+    out->lo = e.lo;
+    out->hi = e.hi;
+    out->slot_offset = e.slot_off;
     return FST_OK;
 }
 

@@ -129,12 +129,11 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     // device tables of every group, uploaded once before any copy is queued
     std::vector<std::vector<LaunchRange>> ranges(ng);
     std::vector<size_t> table_at(ng, 0);
-    std::vector<int64_t> bias(ng, 0);
     std::vector<DevDesc> all;
     for (size_t g = 0; g < ng; ++g) {
         const Group &gr = p->groups[g];
         if (streamed) {
-            const uint64_t need = gr.lo % FST_RAW_ALIGN + (gr.hi - gr.lo);
+            const uint64_t need = gr.slot_bytes;
             if (need > dev_slot_bytes)
                 return fail(FST_E_RANGE, "group %zu needs %llu bytes, device slots have %zu", g,
                             (unsigned long long)need, dev_slot_bytes);
@@ -146,8 +145,7 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
         }
         if (kernels) {
             std::vector<DevDesc> img;
-            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, streamed, img,
-                                     ranges[g], bias[g]))
+            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, streamed, img, ranges[g]))
                 return rc;
             table_at[g] = all.size();
             all.insert(all.end(), img.begin(), img.end());
@@ -164,15 +162,22 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
         HIP_TRY(hipMemcpy(ws, all.data(), all.size() * sizeof(DevDesc), hipMemcpyHostToDevice));
     }
 
-    // cut the groups' byte ranges into blocks of at most one ring slot
+    // cut the groups' staged extents into blocks of at most one ring slot
     std::vector<Block> blocks;
     for (size_t g = 0; g < ng; ++g) {
         const Group &gr = p->groups[g];
-        uint8_t *base = streamed ? static_cast<uint8_t *>(slot_dev[g % n_dev_slots]) + gr.lo % FST_RAW_ALIGN
-                                 : static_cast<uint8_t *>(raw_dev) + p->raw_base[gr.file] + gr.lo;
-        for (uint64_t o = gr.lo; o < gr.hi; o += s->slot_bytes) {
-            const uint64_t len = std::min<uint64_t>(s->slot_bytes, gr.hi - o);
-            blocks.push_back(Block{uint32_t(g), gr.file, o, len, base + (o - gr.lo), o == gr.lo, o + len == gr.hi});
+        const size_t first_block = blocks.size();
+        for (const Extent &ex : gr.extents) {
+            uint8_t *base = streamed ? static_cast<uint8_t *>(slot_dev[g % n_dev_slots]) + ex.slot_off
+                                     : static_cast<uint8_t *>(raw_dev) + p->raw_base[gr.file] + ex.lo;
+            for (uint64_t o = ex.lo; o < ex.hi; o += s->slot_bytes) {
+                const uint64_t len = std::min<uint64_t>(s->slot_bytes, ex.hi - o);
+                blocks.push_back(Block{uint32_t(g), gr.file, o, len, base + (o - ex.lo), false, false});
+            }
+        }
+        if (blocks.size() > first_block) {
+            blocks[first_block].first = true;
+            blocks.back().last = true;
         }
     }
     const size_t nb = blocks.size();
@@ -215,7 +220,7 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
             if (e != hipSuccess) { status = fail(FST_E_HIP, "stream hand-over failed: %s", hipGetErrorString(e)); break; }
             const void *src = streamed ? slot_dev[b.group % n_dev_slots] : raw_dev;
             status = launch_ranges(ranges[b.group], static_cast<const DevDesc *>(ws) + table_at[b.group], src,
-                                   bias[b.group], s->compute);
+                                   s->compute);
             if (status == FST_OK && streamed) {
                 e = hipEventRecord(s->events[1 + b.group % n_dev_slots], s->compute);
                 if (e != hipSuccess) status = fail(FST_E_HIP, "hipEventRecord failed: %s", hipGetErrorString(e));

@@ -86,11 +86,11 @@ def _run_resident(spec, layers, group_bytes=GB):
     return plan
 
 
-def _run_streamed(spec, layers, dev_slots, slot_bytes):
+def _run_streamed(spec, layers, dev_slots, slot_bytes, min_gap=None):
     t0 = time.time()
     model = ProceduralModel(spec)
     plan, names, reqs = _plan(model, spec, [0] * len(model.sizes))
-    ng = plan.set_groups(slot_bytes)
+    ng = plan.set_groups(slot_bytes, min_gap)
     slots = [device.device_bytes(slot_bytes) for _ in range(dev_slots)]
     ws = device.device_bytes(plan.workspace_bytes())
     bufs, ptrs = device.alloc_outputs(plan)
@@ -100,7 +100,7 @@ def _run_streamed(spec, layers, dev_slots, slot_bytes):
                                   ws.data_ptr(), ws.numel())
     finally:
         st.close()
-    print(f"{spec.name}: streamed {stats['staged_bytes'] / 1e9:.2f} GB in {stats['seconds_total']:.2f}s through "
+    print(f"{spec.name}: {'sparse ' if min_gap is not None else ''}streamed {stats['staged_bytes'] / 1e9:.2f} GB in {stats['seconds_total']:.2f}s through "
           f"{dev_slots}x{slot_bytes / GB:.1f} GiB device slots ({ng} groups), outputs {plan.write_bytes() / 1e9:.2f} GB, "
           f"setup {time.time() - t0:.1f}s", flush=True)
     _check_sample(model, spec, plan, bufs, names, reqs, _picks(spec, names, layers))
@@ -120,16 +120,18 @@ def test_config3_llama13b_fp16_to_bf16():
     assert plan.output(5)["dtype"] == "BF16"
 
 
-def test_config4_llama70b_tp8_rank0_streamed():
+@pytest.mark.parametrize("min_gap", [None, 1 << 20])
+def test_config4_llama70b_tp8_rank0_streamed(min_gap):
     spec = specs.config4_llama70b()
-    plan = _run_streamed(spec, layers=[0, 41, 79], dev_slots=3, slot_bytes=4 * GB)
+    plan = _run_streamed(spec, layers=[0, 41, 79], dev_slots=3, slot_bytes=4 * GB, min_gap=min_gap)
     assert plan.output_count() == 723
     assert plan.write_bytes() == 18_163_974_144 == plan.read_bytes()
 
 
-def test_config5_bloom176b_tp8_rank0_streamed():
+@pytest.mark.parametrize("min_gap", [None, 1 << 20])
+def test_config5_bloom176b_tp8_rank0_streamed(min_gap):
     spec = specs.config5_bloom176b()
-    plan = _run_streamed(spec, layers=[0, 35, 69], dev_slots=3, slot_bytes=4 * GB)
+    plan = _run_streamed(spec, layers=[0, 35, 69], dev_slots=3, slot_bytes=4 * GB, min_gap=min_gap)
     assert plan.output_count() == 845
     assert plan.write_bytes() == 50_374_675_456
     # layer norms are widened to fp32: they read 2 bytes and write 4 per element

@@ -39,6 +39,11 @@ def test_random_files(seed):
     _check(got, want, names, reqs, "per-group")
     got, _ = materialize_slots(blobs, names, reqs, rank, world, 16384)
     _check(got, want, names, reqs, "slots")
+    # only the byte ranges the requests read are present (0xDD elsewhere / packed extents in the slot)
+    got, _ = materialize_resident(blobs, names, reqs, rank, world, max_group_bytes=0, min_gap_bytes=0)
+    _check(got, want, names, reqs, "sparse resident")
+    got, _ = materialize_slots(blobs, names, reqs, rank, world, 32768, min_gap_bytes=300)
+    _check(got, want, names, reqs, "sparse slots")
 
 
 # several tiles (a tile is 64 KiB of output) and a ragged tail

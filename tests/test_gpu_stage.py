@@ -48,16 +48,17 @@ class Fds:
             os.close(fd)
 
 
-@pytest.mark.parametrize("seed,slots,threads,slot_bytes,group_bytes", [
-    (0, 3, 4, 4096, 16384), (1, 2, 1, 4096, 4096), (2, 8, 8, 65536, 1 << 20), (3, 1, 3, 8192, 0), (4, 5, 2, 4096, 50000)])
-def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, tmp_path):
+@pytest.mark.parametrize("seed,slots,threads,slot_bytes,group_bytes,gap", [
+    (0, 3, 4, 4096, 16384, None), (1, 2, 1, 4096, 4096, None), (2, 8, 8, 65536, 1 << 20, None), (3, 1, 3, 8192, 0, None),
+    (4, 5, 2, 4096, 50000, None), (5, 3, 4, 4096, 16384, 0), (6, 4, 2, 8192, 0, 1000)])
+def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, gap, tmp_path):
     blobs, paths, names, reqs, rank, world = _case(seed, tmp_path)
     print(f"seed {seed} ring {slots}x{slot_bytes} threads {threads} groups {group_bytes}", flush=True)
     want = oracle_outputs(blobs, names, reqs, rank, world)
     hs = headers_of(blobs)
     bases, raw_len = device.file_bases([len(b) for b in blobs])
     plan = B.Plan(hs, bases, names, reqs, rank, world)
-    plan.set_groups(group_bytes)
+    plan.set_groups(group_bytes, gap)
     raw = device.device_bytes(raw_len)
     raw.fill_(0xCC)
     ws = device.device_bytes(plan.workspace_bytes())
@@ -66,13 +67,17 @@ def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, tmp_path):
     fds = Fds(paths)
     try:
         stats = st.stage_resident(plan, B.read_fds_fn(), fds.ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(), ws.numel())
-        staged = sum(plan.group(g)["hi"] - plan.group(g)["lo"] for g in range(plan.group_count()))
+        staged = sum(plan.group(g)["staged_bytes"] for g in range(plan.group_count()))
         assert stats["staged_bytes"] == staged and stats["n_copies"] >= plan.group_count()
         host = raw.cpu().numpy()
+        covered = np.zeros(raw_len, bool)
         for g in range(plan.group_count()):                     # staged bytes == file bytes
             gi = plan.group(g)
             at = bases[gi["file"]]
-            assert host[at + gi["lo"]:at + gi["hi"]].tobytes() == blobs[gi["file"]][gi["lo"]:gi["hi"]]
+            for lo, hi, _ in gi["extents"]:
+                assert host[at + lo:at + hi].tobytes() == blobs[gi["file"]][lo:hi]
+                covered[at + lo:at + hi] = True
+        assert np.all(host[~covered] == 0xCC)                   # nothing else was written
         for i, w in enumerate(want):
             got = bufs[i][:len(w)].cpu().numpy().tobytes() if len(w) else b""
             assert got == w, f"{names[i]} {reqs[i]}: {first_diff(got, w)}"
@@ -86,15 +91,16 @@ def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, tmp_path):
         st.close()
 
 
-@pytest.mark.parametrize("seed,dev_slots,group_bytes", [(10, 2, 32768), (11, 1, 8192), (12, 3, 100000), (13, 4, 4096)])
-def test_streamed_ring(seed, dev_slots, group_bytes, tmp_path):
+@pytest.mark.parametrize("seed,dev_slots,group_bytes,gap", [(10, 2, 32768, None), (11, 1, 8192, None), (12, 3, 100000, None),
+                                                            (13, 4, 4096, None), (14, 2, 32768, 0), (15, 3, 65536, 2000)])
+def test_streamed_ring(seed, dev_slots, group_bytes, gap, tmp_path):
     """Raw buffer = ring of device slots smaller than the files: groups are cut to fit."""
     blobs, paths, names, reqs, rank, world = _case(seed, tmp_path)
     print(f"seed {seed} device slots {dev_slots}x{group_bytes}", flush=True)
     want = oracle_outputs(blobs, names, reqs, rank, world)
     hs = headers_of(blobs)
     plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
-    ng = plan.set_groups(group_bytes)
+    ng = plan.set_groups(group_bytes, gap)
     assert ng > len(blobs)
     slots = [device.device_bytes(group_bytes) for _ in range(dev_slots)]
     ws = device.device_bytes(plan.workspace_bytes())

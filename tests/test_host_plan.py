@@ -30,7 +30,8 @@ def _interpret(plan, blobs):
         rb_s, rb_d = d["row_elems"] * es_s, d["row_elems"] * es_d
         for r in range(d["n_rows"]):
             lo = d["src_file_off"] + r * d["src_stride"]
-            assert g["lo"] <= lo and lo + rb_s <= g["hi"], "descriptor reads outside its group"
+            assert any(e_lo <= lo and lo + rb_s <= e_hi for e_lo, e_hi, _ in g["extents"]), \
+                "descriptor reads outside the staged extents of its group"
             row = src[lo:lo + rb_s]
             if d["src_dtype"] != d["dst_dtype"]:
                 row = orc.cast_array(row, d["src_dtype"], d["dst_dtype"]).view(np.uint8)
@@ -74,8 +75,9 @@ def test_descriptors_reproduce_the_oracle(seed):
     bases = [4096 * 256 * i for i in range(nfiles)]
     plan = B.Plan(hs, bases, names, reqs, rank, world)
     want = _oracle_outputs(blobs, names, reqs, rank, world)
-    for max_bytes in (0, 4096, 20000, 1 << 20):
-        ng = plan.set_groups(max_bytes)
+    for max_bytes, gap in ((0, None), (4096, None), (20000, None), (1 << 20, None), (0, 0), (0, 4096), (8192, 0),
+                           (50000, 512), (1 << 20, 100000)):
+        ng = plan.set_groups(max_bytes, gap)
         assert ng == plan.group_count()
         got = _interpret(plan, blobs)
         for i, (w, shape, dt) in enumerate(want):
@@ -85,8 +87,18 @@ def test_descriptors_reproduce_the_oracle(seed):
         rd = wr = 0
         for g in range(ng):
             gi = plan.group(g)
-            assert gi["hi"] > gi["lo"] and gi["slot_phase"] == gi["lo"] % 256
-            assert gi["slot_bytes"] == gi["slot_phase"] + gi["hi"] - gi["lo"]
+            assert gi["hi"] > gi["lo"] and gi["n_extents"] == len(gi["extents"]) >= 1
+            at = 0
+            for k, (lo, hi, off) in enumerate(gi["extents"]):
+                assert hi > lo and off % 256 == lo % 256 and off >= at
+                if k:
+                    assert lo > gi["extents"][k - 1][1]
+                    if gap is not None:
+                        assert lo - gi["extents"][k - 1][1] > gap
+                at = off + hi - lo
+            assert gap is not None or gi["n_extents"] == 1
+            assert (gi["extents"][0][0], gi["extents"][-1][1]) == (gi["lo"], gi["hi"])
+            assert gi["staged_bytes"] == sum(hi - lo for lo, hi, _ in gi["extents"]) and at <= gi["slot_bytes"]
             if max_bytes:
                 assert gi["slot_bytes"] <= max_bytes
             rd += gi["read_bytes"]

@@ -16,11 +16,20 @@ def headers_of(blobs):
     return hs
 
 
-def upload_resident(blobs):
+def upload_resident(blobs, sparse_plan=None):
+    """Whole files in the raw buffer; with sparse_plan only that plan's extents (0xDD elsewhere)."""
     bases, raw_len = device.file_bases([len(b) for b in blobs])
-    host = np.zeros(raw_len, np.uint8)
-    for b, at in zip(blobs, bases):
-        host[at:at + len(b)] = np.frombuffer(b, np.uint8)
+    if sparse_plan is None:
+        host = np.zeros(raw_len, np.uint8)
+        for b, at in zip(blobs, bases):
+            host[at:at + len(b)] = np.frombuffer(b, np.uint8)
+    else:
+        host = np.full(raw_len, 0xDD, np.uint8)
+        for g in range(sparse_plan.group_count()):
+            gi = sparse_plan.group(g)
+            for lo, hi, _ in gi["extents"]:
+                at = bases[gi["file"]]
+                host[at + lo:at + hi] = np.frombuffer(blobs[gi["file"]], np.uint8)[lo:hi]
     raw = device.device_bytes(raw_len)
     raw.copy_(torch.from_numpy(host))
     return raw, bases, raw_len
@@ -32,13 +41,14 @@ def fetch(bufs, plan):
             for i in range(plan.output_count())]
 
 
-def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=None, per_group=False, stream=None):
+def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=None, per_group=False, stream=None,
+                         min_gap_bytes=None):
     """Resident layout; one call for all groups, or one call per group."""
     hs = headers_of(blobs)
-    raw, bases, raw_len = upload_resident(blobs)
-    plan = B.Plan(hs, bases, names, reqs, rank, world)
+    plan = B.Plan(hs, device.file_bases([len(b) for b in blobs])[0], names, reqs, rank, world)
     if max_group_bytes is not None:
-        plan.set_groups(max_group_bytes)
+        plan.set_groups(max_group_bytes, min_gap_bytes)
+    raw, bases, raw_len = upload_resident(blobs, plan if min_gap_bytes is not None else None)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
         b.fill_(0xA5)
@@ -54,11 +64,11 @@ def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=No
     return fetch(bufs, plan), plan
 
 
-def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes):
-    """Slot layout: every group's bytes alone in a slot buffer, at the group's phase."""
+def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_bytes=None):
+    """Slot layout: every group's extents alone in a slot buffer, each at its slot offset."""
     hs = headers_of(blobs)
     plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
-    plan.set_groups(max_group_bytes)
+    plan.set_groups(max_group_bytes, min_gap_bytes)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
         b.fill_(0x5A)
@@ -68,7 +78,9 @@ def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes):
         gi = plan.group(g)
         assert gi["slot_bytes"] <= max_group_bytes
         host = np.full(gi["slot_bytes"], 0xEE, np.uint8)
-        host[gi["slot_phase"]:] = np.frombuffer(blobs[gi["file"]], np.uint8)[gi["lo"]:gi["hi"]]
+        for lo, hi, off in gi["extents"]:
+            assert off % 256 == lo % 256
+            host[off:off + hi - lo] = np.frombuffer(blobs[gi["file"]], np.uint8)[lo:hi]
         slot[:gi["slot_bytes"]].copy_(torch.from_numpy(host))
         B.fst_materialize_slot(slot.data_ptr(), gi["slot_bytes"], plan, g, ptrs, ws.data_ptr(), ws.numel(), 0)
         torch.cuda.synchronize()
