@@ -127,12 +127,16 @@ void fst_header_free(fst_header *h);
  *              row-wise split of an output projection = dim 1 (Section II-A).
  *   blocks     1, or b > 1 with shard_dim 0: dimension 0 is b stacked sub-tensors (fused QKV);
  *              each is split by rank and the rank's parts are concatenated in block order.
+ *   rank       -1 = the rank given to fst_plan_create; r >= 0 = this request is rank r's share.
+ *              Asking for one name once per rank yields every rank's share from one pass over
+ *              the raw bytes: the single-GPU half of the paper's scatter (Section III-B, Fig. 6).
  * shape[shard_dim] must be divisible by blocks*world (FST_E_SHARD otherwise; no padding).
  */
 typedef struct fst_request {
     int32_t dst_dtype;
     int32_t shard_dim;
     int32_t blocks;
+    int32_t rank;
 } fst_request;
 
 /*

@@ -33,7 +33,7 @@ class fst_tensor_info(Structure):
 
 
 class fst_request(Structure):
-    _fields_ = [("dst_dtype", c_int32), ("shard_dim", c_int32), ("blocks", c_int32)]
+    _fields_ = [("dst_dtype", c_int32), ("shard_dim", c_int32), ("blocks", c_int32), ("rank", c_int32)]
 
 
 class fst_output_info(Structure):
@@ -212,7 +212,8 @@ class Header:
             pass
 
 
-Request = Tuple[Optional[str], int, int]    # (dst dtype name or None, shard_dim, blocks)
+# (dst dtype name or None, shard_dim, blocks) or (dst dtype, shard_dim, blocks, rank of this request)
+Request = Tuple
 
 
 class Plan:
@@ -225,8 +226,8 @@ class Plan:
         rb = (c_uint64 * n_files)(*raw_base)
         nm = (c_char_p * max(n, 1))(*[s.encode("utf-8") for s in names])
         rq = (fst_request * max(n, 1))()
-        for i, (dt, dim, blocks) in enumerate(requests):
-            rq[i] = fst_request(fst_dtype(dt), dim, blocks)
+        for i, r in enumerate(requests):
+            rq[i] = fst_request(fst_dtype(r[0]), r[1], r[2], r[3] if len(r) > 3 else -1)
         self._p = c_void_p()
         _check(lib().fst_plan_create(hs, rb, n_files, nm, rq, n, rank, world, byref(self._p)))
         self.names = list(names)

@@ -313,6 +313,8 @@ int plan_impl(const fst_header *const *hdrs, const uint64_t *raw_base, size_t n_
         if (rq.blocks < 1 || (d < 0 && rq.blocks != 1) || (rq.blocks > 1 && d != 0))
             return fail(FST_E_SHARD, "%s: blocks=%d needs shard_dim 0", names[i], rq.blocks);
         if (d >= t->ndim) return fail(FST_E_SHARD, "%s: shard_dim %d but the tensor has %d dims", names[i], d, t->ndim);
+        const int32_t req_rank = rq.rank < 0 ? rank : rq.rank;
+        if (req_rank >= world) return fail(FST_E_SHARD, "%s: rank %d is not inside world %d", names[i], req_rank, world);
 
         Output &o = p->outputs[i];
         o.info = fst_output_info{};
@@ -344,7 +346,7 @@ int plan_impl(const fst_header *const *hdrs, const uint64_t *raw_base, size_t n_
             o.n_rows = outer * uint64_t(rq.blocks);
             o.row_elems = per * inner;
             o.src_stride = (t->shape[d] / uint64_t(rq.blocks)) * inner * es;
-            o.src_file_off = o.tensor_begin + uint64_t(rank) * per * inner * es;
+            o.src_file_off = o.tensor_begin + uint64_t(req_rank) * per * inner * es;
             numel = o.n_rows * o.row_elems;
             if (o.n_rows > 1 && o.src_stride == o.row_elems * es) {   // rows are back to back
                 o.row_elems *= o.n_rows;
@@ -384,7 +386,7 @@ int fst_plan_uniform(const fst_header *const *hdrs, const uint64_t *raw_base, si
                      int32_t rank, int32_t world, fst_plan **out)
 {
     try {
-        std::vector<fst_request> reqs(n_names, fst_request{dst_dtype, shard_dim, 1});
+        std::vector<fst_request> reqs(n_names, fst_request{dst_dtype, shard_dim, 1, -1});
         return plan_impl(hdrs, raw_base, n_files, names, reqs.data(), n_names, rank, world, out);
     } catch (const std::bad_alloc &) {
         return fail(FST_E_NOMEM, "out of memory");

@@ -199,10 +199,53 @@ def config5_bloom176b(layers: int = 70, h: int = 14336, vocab: int = 250880) -> 
     return ModelSpec("bloom-176b", 5, files, world=8, rank=0)
 
 
+def _falcon_layer(i: int, h: int, qkv_rows: int, dt: str, tp: bool) -> List[TensorSpec]:
+    p = f"transformer.h.{i}."
+    col = 0 if tp else -1
+    row = 1 if tp else -1
+    return [
+        TensorSpec(p + "ln_attn.weight", dt, (h,), fill="ones"),
+        TensorSpec(p + "ln_attn.bias", dt, (h,)),
+        TensorSpec(p + "ln_mlp.weight", dt, (h,), fill="ones"),
+        TensorSpec(p + "ln_mlp.bias", dt, (h,)),
+        # fused QKV stored group by group (per KV group: its query heads, one key head, one value
+        # head): a plain split of dim 0 hands each rank whole groups
+        TensorSpec(p + "self_attention.query_key_value.weight", dt, (qkv_rows, h), shard_dim=col),
+        TensorSpec(p + "self_attention.dense.weight", dt, (h, h), shard_dim=row),
+        TensorSpec(p + "mlp.dense_h_to_4h.weight", dt, (4 * h, h), shard_dim=col),
+        TensorSpec(p + "mlp.dense_4h_to_h.weight", dt, (h, 4 * h), shard_dim=row),
+    ]
+
+
+def config_falcon40b(layers: int = 60, nfiles: int = 9, world: int = 2) -> ModelSpec:
+    """Falcon-40B-shaped checkpoint (Table I: 9 files, 78 GiB): 60 layers, hidden 8192, 128 query heads
+    and 8 key/value heads of 64, vocabulary 65024, bf16; rank 0 of a 2-way split (the paper loads it
+    on two GPUs)."""
+    h, dt, vocab = 8192, "BF16", 65024
+    qkv_rows = (128 + 2 * 8) * 64
+    per, extra = divmod(layers, nfiles)
+    files, at = [], 0
+    for f in range(nfiles):
+        n = per + (1 if f < extra else 0)
+        ts: List[TensorSpec] = []
+        if f == 0:
+            ts.append(TensorSpec("transformer.word_embeddings.weight", dt, (vocab, h)))
+        for i in range(at, at + n):
+            ts += _falcon_layer(i, h, qkv_rows, dt, world > 1)
+        at += n
+        if f == nfiles - 1:
+            ts.append(TensorSpec("transformer.ln_f.weight", dt, (h,), fill="ones"))
+            ts.append(TensorSpec("transformer.ln_f.bias", dt, (h,)))
+            ts.append(TensorSpec("lm_head.weight", dt, (vocab, h)))
+        files.append(FileSpec(f"model-{f + 1:05d}-of-{nfiles:05d}.safetensors", ts, _RESIDUES[(f + 5) % 16]))
+    return ModelSpec("falcon-40b", 6, files, world=world, rank=0)
+
+
 CONFIGS = {
     "tiny": config1_tiny,
     "llama-7b": config2_llama7b,
     "llama-13b": config3_llama13b,
     "llama-70b": config4_llama70b,
     "bloom-176b": config5_bloom176b,
+    "falcon-40b": config_falcon40b,
 }

@@ -32,7 +32,7 @@ def test_binding_covers_every_declared_symbol():
 def test_struct_sizes_match_the_header():
     # sizes follow from the field lists in fst.h (natural alignment, 8-byte max)
     assert ctypes.sizeof(B.fst_tensor_info) == 8 + 8 + 4 + 4 + 64 + 8 + 8
-    assert ctypes.sizeof(B.fst_request) == 12
+    assert ctypes.sizeof(B.fst_request) == 16
     assert ctypes.sizeof(B.fst_output_info) == 4 + 4 + 64 + 8 + 4 + 4
     assert ctypes.sizeof(B.fst_group_info) == 4 * 4 + 8 * 6
     assert ctypes.sizeof(B.fst_extent) == 24

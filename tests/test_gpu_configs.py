@@ -136,3 +136,13 @@ def test_config5_bloom176b_tp8_rank0_streamed(min_gap):
     assert plan.write_bytes() == 50_374_675_456
     # layer norms are widened to fp32: they read 2 bytes and write 4 per element
     assert plan.write_bytes() - plan.read_bytes() == 16_285_696 // 2
+
+
+def test_falcon40b_tp2_rank0_streamed_sparse():
+    """A second workload from the paper's Table I (Falcon-40B, 9 files, loaded on two GPUs there)."""
+    spec = specs.config_falcon40b()
+    assert spec.n_tensors == 60 * 8 + 4 and abs(spec.body_bytes / 2 ** 30 - 78) < 1.0
+    plan = _run_streamed(spec, layers=[0, 30, 59], dev_slots=3, slot_bytes=4 * GB, min_gap=1 << 20)
+    whole = sum(t.nbytes for f in spec.files for t in f.tensors if t.shard_dim < 0)
+    split = sum(t.nbytes for f in spec.files for t in f.tensors if t.shard_dim >= 0)
+    assert plan.write_bytes() == whole + split // 2 == plan.read_bytes()

@@ -145,6 +145,26 @@ def test_f32_conversions_on_device(dst):
         assert got[0] == want, f"F32->{dst} lead {lead}: {first_diff(got[0], want)}"
 
 
+def test_all_ranks_in_one_pass():
+    """Every rank's share of every tensor from one plan and one launch set (per-request rank)."""
+    rng = np.random.default_rng(21)
+    ts = [("q", "BF16", (512, 264), random_bits(rng, "BF16", (512, 264)).tobytes()),
+          ("o", "F16", (264, 512), random_bits(rng, "F16", (264, 512)).tobytes()),
+          ("qkv", "BF16", (3 * 128, 72), random_bits(rng, "BF16", (384, 72)).tobytes()),
+          ("norm", "BF16", (264,), random_bits(rng, "BF16", (264,)).tobytes())]
+    blob = writer.write_file(None, ts, None, 13)
+    world = 8
+    names, reqs = ["norm"], [("F32", -1, 1)]
+    for r in range(world):
+        names += ["q", "o", "qkv"]
+        reqs += [(None, 0, 1, r), ("BF16", 1, 1, r), ("F32", 0, 3, r)]
+    want = oracle_outputs([blob], names, reqs, 0, world)
+    got, plan = materialize_resident([blob], names, reqs, 0, world)
+    _check(got, want, names, reqs, "all ranks")
+    assert b"".join(got[1 + 3 * r] for r in range(world)) == ts[0][3]       # q shares = stored q
+    assert plan.read_bytes() == sum(len(t[3]) for t in ts)                    # every stored byte read once
+
+
 def test_on_a_side_stream_and_empty_plan():
     rng = np.random.default_rng(3)
     blob, ts = make_file(rng, n_tensors=6, big=True)

@@ -174,3 +174,46 @@ def test_tiny_checkpoint_end_to_end(tmp_path):
 def test_smoke_entry_point():
     import __graft_entry__
     __graft_entry__.smoke()
+
+
+def test_loader_api(tmp_path):
+    """The paper-shaped Python API (Figs. 8/9) over the C ABI: whole tensors, shards, conversions."""
+    from oracle import oracle as orc
+    from paper_2505_23072_amd.loader import FilesBufferOnDevice, LocalShard, SafeTensorsFileLoader, SingleGroup
+    blobs, paths, names, reqs, rank, world = _case(30, tmp_path, nfiles=2)
+    loader = SafeTensorsFileLoader(SingleGroup(), torch.device("cuda:0"))
+    loader.add_filenames({0: paths})
+    fb = loader.copy_files_to_device()
+    assert sorted(fb.keys()) == sorted(names)
+    want = oracle_outputs(blobs, names, [(None, -1, 1)] * len(names))
+    for n, w in zip(names, want):
+        t = fb.get_tensor(n)
+        assert t.contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes() == w if len(w) else t.numel() == 0
+    fb.close()
+    with pytest.raises(RuntimeError):
+        fb.get_tensor(names[0])
+    # rank 1 of 2: shards and conversions in one launch set; auto release after the last key
+    sh = SafeTensorsFileLoader(LocalShard(1, 2), torch.device("cuda:0"), auto_release=True)
+    sh.add_filenames({0: paths[:1], 1: paths[1:]})
+    fb = sh.copy_files_to_device()
+    rq = {n: r for n, r in zip(names, [random_request(np.random.default_rng(i), d, s, 2)
+                                       for i, (n_, d, s) in enumerate(_specs_of(blobs))])}
+    got = fb.get_many(rq)
+    want = oracle_outputs(blobs, list(rq), list(rq.values()), 1, 2)
+    for (n, t), w in zip(got.items(), want):
+        gb = t.contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes() if t.numel() else b""
+        assert gb == w, n
+    with pytest.raises(RuntimeError):      # every key fetched: the raw buffer is gone
+        fb.get_tensor(names[0])
+    loader.close()
+    sh.close()
+
+
+def _specs_of(blobs):
+    from oracle import oracle as orc
+    out = []
+    for b in blobs:
+        for t in orc.parse(b, len(b)).tensors:
+            out.append((t.name, t.dtype, t.shape))
+    # same order as `names` in _case: file by file, in on-disk order
+    return out

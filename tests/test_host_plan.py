@@ -46,14 +46,16 @@ def _interpret(plan, blobs):
 def _oracle_outputs(blobs, names, reqs, rank, world):
     tabs = [orc.parse(b, len(b)) for b in blobs]
     res = []
-    for nm, (dst, dim, blocks) in zip(names, reqs):
+    for nm, rq in zip(names, reqs):
+        dst, dim, blocks = rq[:3]
+        r = rq[3] if len(rq) > 3 and rq[3] >= 0 else rank
         for b, tab in zip(blobs, tabs):
             try:
                 t = tab.find(nm)
             except orc.OracleError:
                 continue
             stored = np.frombuffer(b, np.uint8, t.end - t.begin, tab.body_off + t.begin)
-            out, shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, rank, world)
+            out, shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, r, world)
             res.append((out.tobytes(), shape, dst or t.dtype))
             break
     return res
@@ -188,3 +190,30 @@ def test_uniform_plan_matches_per_name_requests():
     e = B.Plan(h, [0], ["p", "q"], [("BF16", 0, 1)] * 2, 1, 2)
     assert [u.descriptor(i) for i in range(2)] == [e.descriptor(i) for i in range(2)]
     assert [u.output(i) for i in range(2)] == [e.output(i) for i in range(2)]
+
+
+def test_every_ranks_share_from_one_plan():
+    """One request per (name, rank): the plan yields all shares; together they are the stored tensor."""
+    from synth import writer
+    rng = np.random.default_rng(8)
+    w = rng.integers(0, 1 << 16, (48, 40), dtype=np.uint16)
+    qkv = rng.integers(0, 1 << 16, (72, 8), dtype=np.uint16)
+    blob = writer.write_file(None, [("w", "F16", (48, 40), w.tobytes()), ("qkv", "F16", (72, 8), qkv.tobytes())], None, 5)
+    h = _headers([blob])
+    world = 4
+    names, reqs = [], []
+    for r in range(world):
+        names += ["w", "w", "qkv"]
+        reqs += [(None, 0, 1, r), ("BF16", 1, 1, r), (None, 0, 3, r)]
+    plan = B.Plan(h, [0], names, reqs, rank=0, world=world)
+    got = _interpret(plan, [blob])
+    want = _oracle_outputs([blob], names, reqs, 0, world)
+    assert [g for g in got] == [x[0] for x in want]
+    # dim-0 shares concatenated give back the stored matrix
+    rows = b"".join(got[3 * r] for r in range(world))
+    assert rows == w.tobytes()
+    # every stored byte of w and qkv is read exactly twice (w) / once (qkv)
+    assert plan.read_bytes() == 2 * w.nbytes + qkv.nbytes
+    with pytest.raises(B.FstError) as e:
+        B.Plan(h, [0], ["w"], [(None, 0, 1, 4)], 0, world)
+    assert e.value.name == "FST_E_SHARD"

@@ -90,14 +90,16 @@ def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_
 def oracle_outputs(blobs, names, reqs, rank=0, world=1):
     tabs = [orc.parse(bytes(b), len(b)) for b in blobs]
     res = []
-    for nm, (dst, dim, blocks) in zip(names, reqs):
+    for nm, rq in zip(names, reqs):
+        dst, dim, blocks = rq[:3]
+        r = rq[3] if len(rq) > 3 and rq[3] >= 0 else rank
         for b, tab in zip(blobs, tabs):
             hit = [t for t in tab.tensors if t.name == nm]
             if not hit:
                 continue
             t = hit[0]
             stored = np.frombuffer(b, np.uint8, t.end - t.begin, tab.body_off + t.begin)
-            out, shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, rank, world)
+            out, shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, r, world)
             res.append(out.tobytes())
             break
         else:
