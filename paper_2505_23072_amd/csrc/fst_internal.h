@@ -50,11 +50,13 @@ struct DevDesc {
     uint64_t src_stride;     // bytes between rows
     uint64_t dst;            // device address of the first output byte of this piece
     uint64_t n_units;        // VEC: chunks in total (rows * units_per_row); ELEM: elements
-    uint32_t units_per_row;  // VEC: chunks per row; ELEM: elements per row
+    uint32_t units_per_row;  // VEC: chunks per row (0 = one row of any length); ELEM: elements per row
     uint32_t tile0;          // index of this piece's first tile inside its launch
     uint32_t n_tiles;
+    uint32_t div_m;          // division by units_per_row as a multiplication: see fast_div
+    uint32_t div_s;          //   (0 = divisor is 1)
     uint32_t pad0;
-    uint64_t pad1, pad2;
+    uint64_t pad1;
 };
 static_assert(sizeof(DevDesc) == 64, "DevDesc is 64 bytes");
 
@@ -83,6 +85,7 @@ struct Group {
     uint64_t slot_bytes = 0;                // slot space the extents take
     size_t desc_begin = 0, desc_end = 0;    // public descriptors [begin, end)
     std::vector<Piece> pieces;              // sorted by launch class
+    size_t hint_bound = 0;                  // upper bound of this group's hint entries
     uint64_t read_bytes = 0, write_bytes = 0;
 };
 
@@ -106,9 +109,11 @@ inline uint32_t launch_class(const Piece &p)
 
 // Geometry of the kernels, fixed at compile time and needed by the planner to count tiles.
 // The vector kernels run 1024-thread workgroups (16 wavefronts) in which every lane moves
-// VEC_UNROLL chunks: one tile = 4096 chunks = 64 KiB of 16-byte chunks.
+// VEC_UNROLL chunks: one tile = 1024 chunks = 16 KiB of 16-byte chunks.  One chunk per lane
+// measured fastest: many short-lived wavefronts keep more requests in flight than fewer
+// wavefronts with several loads each.
 constexpr uint32_t VEC_BLOCK_THREADS = 1024;
-constexpr uint32_t VEC_UNROLL = 4;                       // chunks in flight per thread
+constexpr uint32_t VEC_UNROLL = 1;                       // chunks per thread
 constexpr uint32_t VEC_TILE_UNITS = VEC_BLOCK_THREADS * VEC_UNROLL;           // chunks per tile
 constexpr uint32_t ELEM_BLOCK_THREADS = 256;
 constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 // elements per tile
@@ -116,12 +121,34 @@ constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 //
 // works on runs of XCD_RUN consecutive tiles (1 MiB of output), which measured faster than both
 // tile-by-tile interleaving and giving each XCD one contiguous eighth.
 constexpr uint32_t XCD_COUNT = 8;
-constexpr uint32_t XCD_RUN = 16;
+constexpr uint32_t XCD_RUN = 64;
+// A workgroup finds its piece through a hint table with one entry per HINT_SPAN tiles (the piece
+// that holds the span's first tile) and then steps forward; for large tensors that is no step.
+constexpr uint32_t HINT_SPAN = 64;
+// Vector pieces are cut so that chunk indices inside a piece fit 32 bits.
+constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;
 
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
 uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)
 uint32_t conv_dst_bytes(uint32_t conv);
 uint32_t conv_chunk_elems(uint32_t conv);                     // 16 (bytes) for COPY, 8 otherwise
+
+// One kernel launch: pieces [first, first+count) of a device table, all of one launch class, with
+// their hint entries [hint_first, ...).
+struct LaunchRange { uint32_t cls, first, count, tiles, hint_first; };
+// Host copy of a device table: pieces, hints, and the launches over them.
+struct TableImage {
+    std::vector<DevDesc> descs;
+    std::vector<uint32_t> hints;      // per launch: for tile HINT_SPAN*k, the piece (from the launch's first) holding it
+    std::vector<LaunchRange> ranges;
+    std::vector<uint8_t> blob;        // what is copied to the device: descs, then hints at table_hint_offset
+};
+// Bytes a table occupies in the workspace: pieces first, hints after them on a 256-byte boundary.
+inline size_t table_hint_offset(size_t n_descs) { return (n_descs * sizeof(DevDesc) + 255) / 256 * 256; }
+inline size_t table_bytes(size_t n_descs, size_t n_hints)
+{
+    return (table_hint_offset(n_descs) + n_hints * sizeof(uint32_t) + 255) / 256 * 256;
+}
 
 }  // namespace fst
 
@@ -140,21 +167,19 @@ struct fst_plan {
     // for "all groups").  They belong to the plan so that an enqueued upload never outlives its
     // source; re-cutting the groups drops them.
     mutable std::mutex image_mu;
-    mutable std::map<size_t, std::vector<fst::DevDesc>> images;
+    mutable std::map<size_t, fst::TableImage> images;
 };
 
 namespace fst {
 int build_groups(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes);
 
-// One kernel launch: pieces [first, first+count) of a device table, all of one launch class.
-struct LaunchRange { uint32_t cls, first, count, tiles; };
 // Device table for groups [g0, g1) merged into one launch set.  slot: address sources for the
 // slot layout of group g0 (then g1 == g0+1) instead of the resident layout.
 int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
-                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges);
-int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev,
-                  void *stream);
-// Launch the kernels of one class.  descs_dev: the class's DevDesc array on the device.
-int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
+                TableImage &image);
+// table_dev: where image.blob was copied.
+int launch_ranges(const TableImage &image, const void *table_dev, const void *src_dev, void *stream);
+// Launch the kernels of one class.  descs_dev / hints_dev: the class's arrays on the device.
+int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
                          const void *raw_dev, void *stream);
 }  // namespace fst

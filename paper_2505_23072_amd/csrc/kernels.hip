@@ -3,11 +3,11 @@
 // partition is taken in the same pass).  Pure data movement: HBM-bound, no matrix cores.
 //
 // Work is a table of pieces (DevDesc).  One workgroup of 1024 threads = 16 wavefronts takes one
-// tile of a piece; the piece is found by a binary search over the table's tile prefix, done with
-// scalar loads since it only depends on the workgroup index.  In the vector path a lane moves one
-// chunk at a time: 16 source bytes when nothing is converted, 8 elements otherwise, always
-// written with full 16-byte stores to a 16-byte aligned destination.  Several chunks per lane are
-// loaded before the first store so that enough reads are in flight to cover HBM latency.
+// tile of a piece; the piece is found through a hint table (one entry per HINT_SPAN tiles) with
+// scalar loads, since it only depends on the workgroup index.  In the vector path a lane moves one
+// chunk: 16 source bytes when nothing is converted, 8 elements otherwise, always written with
+// full 16-byte stores to a 16-byte aligned destination.  Latency is covered by occupancy (two
+// workgroups = 32 wavefronts per CU), not by several loads per lane.
 //
 // The source may start at any byte.  Sources that are a multiple of 4 are read with 4-byte
 // aligned 16-byte loads.  Others read the enclosing aligned dwords (one more than the chunk
@@ -205,50 +205,43 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
     return o;
 }
 
-// The piece that owns tile `b`: last entry whose first tile is <= b.
-__device__ __forceinline__ uint32_t find_piece(const DevDesc *__restrict__ descs, uint32_t n_desc, uint32_t b)
+// The piece that owns tile `b`: the hint names the piece that holds the first tile of b's span of
+// HINT_SPAN tiles; the owner is that piece or one of the next few (none for a large tensor).
+// Every tile index below the launch's tile count belongs to a piece, so the walk ends.
+__device__ __forceinline__ const DevDesc *find_piece(const DevDesc *__restrict__ descs,
+                                                     const uint32_t *__restrict__ hints, uint32_t b)
 {
-    uint32_t lo = 0, hi = n_desc;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (descs[mid].tile0 <= b) lo = mid; else hi = mid;
-    }
-    return lo;
+    const DevDesc *d = descs + hints[b / HINT_SPAN];
+    while (b - d->tile0 >= d->n_tiles) ++d;
+    return d;
 }
 
-// One tile: chunk i of the tile (i < n) is read at `src` + its row/column offset and written at
-// dst + i*CD.  FULL: the tile has all VEC_TILE_UNITS chunks, so no lane needs a bounds check.
-template <uint32_t CONV, bool BYTE, bool FULL>
-__device__ __forceinline__ void vec_tile(const uint8_t *src, uint8_t *dst, uint32_t n, uint32_t upr, uint32_t col0,
-                                         uint64_t stride)
+// n / d for n < 2^31 with the multiplier the host derived from d (see division_magic).
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t m, uint32_t s)
+{
+    return __umulhi(n << 1, m) >> s;
+}
+
+// One chunk per lane: chunk c of the piece (c < n_units) is read at its row/column offset from
+// `src` and written at dst + c*CD.
+template <uint32_t CONV, bool BYTE>
+__device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint32_t c, const DevDesc *d)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
-    Chunk32 v[VEC_UNROLL];
-#pragma unroll
-    for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
-        const uint32_t i = u * VEC_BLOCK_THREADS + threadIdx.x;
-        if (FULL || i < n) {
-            const uint8_t *s;
-            if (upr == 0) {
-                s = src + uint64_t(i) * CS;
-            } else {
-                const uint32_t cc = col0 + i;                        // chunk index from the row start
-                const uint32_t r = cc / upr;
-                s = src + uint64_t(r) * stride + uint64_t(cc - r * upr) * CS;
-            }
-            if (CS == 16) v[u].lo = load16<BYTE>(s); else v[u] = load32<BYTE>(s);
-        }
+    const uint32_t upr = d->units_per_row;
+    const uint8_t *s;
+    if (upr == 0) {
+        s = src + uint64_t(c) * CS;                                  // one row of any length
+    } else {
+        const uint32_t r = fast_div(c, d->div_m, d->div_s);
+        s = src + uint64_t(r) * d->src_stride + uint64_t(c - r * upr) * CS;
     }
-#pragma unroll
-    for (uint32_t u = 0; u < VEC_UNROLL; ++u) {
-        const uint32_t i = u * VEC_BLOCK_THREADS + threadIdx.x;
-        if (FULL || i < n) {
-            const Chunk32 o = convert_chunk<CONV>(v[u]);
-            uint8_t *t = dst + uint64_t(i) * CD;
-            gstore16(t, o.lo);
-            if (CD == 32) gstore16(t + 16, o.hi);
-        }
-    }
+    Chunk32 v;
+    if (CS == 16) v.lo = load16<BYTE>(s); else v = load32<BYTE>(s);
+    const Chunk32 o = convert_chunk<CONV>(v);
+    uint8_t *t = dst + uint64_t(c) * CD;
+    gstore16(t, o.lo);
+    if (CD == 32) gstore16(t + 16, o.hi);
 }
 
 // Workgroup index -> tile index.  Workgroup i runs on XCD i % 8; within every span of 8*XCD_RUN
@@ -262,45 +255,31 @@ __device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_wg
 }
 
 template <uint32_t CONV, bool BYTE>
-__global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs, uint32_t n_desc,
+__global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs,
+                                                                     const uint32_t *__restrict__ hints,
                                                                      const uint8_t *__restrict__ raw)
 {
-    constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
-    const DevDesc *d = descs + find_piece(descs, n_desc, b);
+    const DevDesc *d = find_piece(descs, hints, b);
     const uint32_t t = b - d->tile0;                                    // tile inside the piece
-    const uint64_t c0 = uint64_t(t) * VEC_TILE_UNITS;                   // first chunk of this tile
+    const uint32_t c0 = t * VEC_TILE_UNITS;                             // a piece has at most 2^31 chunks
     // only a piece's last tile can be short; decided on 32-bit tile counts
-    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units - c0) : VEC_TILE_UNITS;
-    const uint32_t upr = d->units_per_row;
-    const uint64_t stride = d->src_stride;
-    uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + c0 * CD;
-    const uint8_t *src = raw + d->src_off;
-    uint32_t col0 = 0;
-    if (upr == 0) {
-        src += c0 * CS;                                                  // one row of any length
-    } else {
-        const uint64_t row0 = c0 / upr;
-        col0 = uint32_t(c0 - row0 * upr);
-        src += row0 * stride;
-    }
-
-    if (n == VEC_TILE_UNITS)
-        vec_tile<CONV, BYTE, true>(src, dst, n, upr, col0, stride);
-    else
-        vec_tile<CONV, BYTE, false>(src, dst, n, upr, col0, stride);
+    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units) - c0 : VEC_TILE_UNITS;
+    if (threadIdx.x < n)
+        vec_chunk<CONV, BYTE>(raw + d->src_off, reinterpret_cast<uint8_t *>(d->dst), c0 + threadIdx.x, d);
 }
 
 // Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
 // byte when nothing is converted) per thread and step; sources are read bytewise.
 template <uint32_t CONV>
-__global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs, uint32_t n_desc,
-                                                                  const uint8_t *__restrict__ raw)
+__global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
+                                                                       const uint32_t *__restrict__ hints,
+                                                                       const uint8_t *__restrict__ raw)
 {
     constexpr uint32_t ES = CONV == CONV_COPY ? 1 : (CONV == CONV_F2H || CONV == CONV_F2B) ? 4 : 2;
     constexpr uint32_t ED = CONV == CONV_COPY ? 1 : (CONV == CONV_H2F || CONV == CONV_B2F) ? 4 : 2;
     const uint32_t b = blockIdx.x;
-    const DevDesc *d = descs + find_piece(descs, n_desc, b);
+    const DevDesc *d = find_piece(descs, hints, b);
     const uint32_t t = b - d->tile0;
     const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
     const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units - e0) : ELEM_TILE_UNITS;
@@ -325,16 +304,16 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
 }
 
 template <uint32_t CONV>
-int launch_conv(uint32_t variant, const DevDesc *descs, uint32_t n_desc, uint32_t n_tiles, const uint8_t *raw,
+int launch_conv(uint32_t variant, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles, const uint8_t *raw,
                 hipStream_t stream)
 {
     const dim3 grid(n_tiles);
     if (variant == 0)
-        hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
+        hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
     else if (variant == 1)
-        hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
+        hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
     else
-        hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, n_desc, raw);
+        hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return FST_OK;
@@ -342,23 +321,23 @@ int launch_conv(uint32_t variant, const DevDesc *descs, uint32_t n_desc, uint32_
 
 }  // namespace
 
-int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, uint32_t n_desc, uint32_t n_tiles,
+int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
                          const void *raw_dev, void *stream)
 {
-    if (n_desc == 0 || n_tiles == 0) return FST_OK;
+    if (n_tiles == 0) return FST_OK;
     uint32_t conv, variant;
     if (cls < CONV_COUNT * 2) { conv = cls / 2; variant = cls % 2; }
     else { conv = cls - CONV_COUNT * 2; variant = 2; }
     const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (conv) {
-    case CONV_COPY: return launch_conv<CONV_COPY>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_H2B: return launch_conv<CONV_H2B>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_B2H: return launch_conv<CONV_B2H>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_H2F: return launch_conv<CONV_H2F>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_B2F: return launch_conv<CONV_B2F>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_F2H: return launch_conv<CONV_F2H>(variant, descs_dev, n_desc, n_tiles, raw, s);
-    case CONV_F2B: return launch_conv<CONV_F2B>(variant, descs_dev, n_desc, n_tiles, raw, s);
+    case CONV_COPY: return launch_conv<CONV_COPY>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_H2B: return launch_conv<CONV_H2B>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_B2H: return launch_conv<CONV_B2H>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_H2F: return launch_conv<CONV_H2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_B2F: return launch_conv<CONV_B2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2H: return launch_conv<CONV_F2H>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2B: return launch_conv<CONV_F2B>(variant, descs_dev, hints_dev, n_tiles, raw, s);
     default: return fail(FST_E_ARG, "unknown launch class %u", cls);
     }
 }

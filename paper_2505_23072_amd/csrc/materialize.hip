@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
 #include <mutex>
 #include <new>
 
@@ -19,22 +20,35 @@ uint32_t tiles_of(const Piece &pc)
     return uint32_t((pc.n_units + per - 1) / per);
 }
 
+// Multiplier m and shift s with floor(n / d) == umulhi(2n, m) >> s for every n < 2^31, d in
+// [1, 2^31]: s = ceil(log2 d), m = ceil(2^(31+s) / d).  m*d exceeds 2^(31+s) by e < d <= 2^s, so
+// n*m / 2^(31+s) exceeds n/d by n*e / (d * 2^(31+s)) < 1/d, too little to reach the next integer.
+void division_magic(uint32_t d, uint32_t &m, uint32_t &s)
+{
+    s = 0;
+    while ((uint64_t(1) << s) < d) ++s;
+    m = uint32_t(((uint64_t(1) << (31 + s)) + d - 1) / d);
+}
+
 }  // namespace
 
 // Builds the device image for groups [g0, g1) as ONE launch set (pieces of all those groups
 // merged per class).  slot = true: sources are addressed for the slot layout of group g0 (g1 must
 // be g0+1): a piece's bytes are found through the extent that holds them.
 int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
-                std::vector<DevDesc> &image, std::vector<LaunchRange> &ranges)
+                TableImage &image)
 {
+    std::vector<DevDesc> &descs = image.descs;
+    std::vector<LaunchRange> &ranges = image.ranges;
     std::vector<const Piece *> order;
     for (size_t g = g0; g < g1; ++g)
         for (const Piece &pc : p->groups[g].pieces) order.push_back(&pc);
     std::stable_sort(order.begin(), order.end(),
                      [](const Piece *a, const Piece *b) { return launch_class(*a) < launch_class(*b); });
-    image.clear();
+    descs.clear();
     ranges.clear();
-    image.reserve(order.size());
+    image.hints.clear();
+    descs.reserve(order.size());
     for (const Piece *pc : order) {
         const Output &o = p->outputs[pc->output];
         const uintptr_t out = reinterpret_cast<uintptr_t>(out_ptrs[pc->output]);
@@ -61,7 +75,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
             return fail(FST_E_RANGE, "output %u reads bytes [%llu, %llu) but the buffer has %zu", pc->output,
                         (unsigned long long)src_off, (unsigned long long)(src_off + pc->src_span), src_len);
         const uint32_t cls = launch_class(*pc);
-        if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(image.size()), 0, 0});
+        if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(descs.size()), 0, 0, 0});
         LaunchRange &r = ranges.back();
         DevDesc d{};
         d.src_off = src_off;
@@ -71,18 +85,39 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         d.units_per_row = pc->units_per_row;
         d.tile0 = r.tiles;
         d.n_tiles = tiles_of(*pc);
+        if (pc->path == PATH_VEC && pc->units_per_row) division_magic(pc->units_per_row, d.div_m, d.div_s);
         if (uint64_t(r.tiles) + d.n_tiles > 0x7FFFFFFFull) return fail(FST_E_RANGE, "too many tiles in one launch");
         r.tiles += d.n_tiles;
         r.count += 1;
-        image.push_back(d);
+        descs.push_back(d);
     }
+    // hints: for every HINT_SPAN-th tile of a launch, the piece (counted from the launch's first)
+    // that holds it
+    for (LaunchRange &r : ranges) {
+        r.hint_first = uint32_t(image.hints.size());
+        uint32_t at = 0;
+        for (uint32_t t = 0; t < r.tiles; t += HINT_SPAN) {
+            while (t - descs[r.first + at].tile0 >= descs[r.first + at].n_tiles) ++at;
+            image.hints.push_back(at);
+        }
+    }
+    // one blob for the upload: pieces, then hints on a 256-byte boundary
+    image.blob.assign(table_bytes(descs.size(), image.hints.size()), 0);
+    if (!descs.empty()) std::memcpy(image.blob.data(), descs.data(), descs.size() * sizeof(DevDesc));
+    if (!image.hints.empty())
+        std::memcpy(image.blob.data() + table_hint_offset(descs.size()), image.hints.data(),
+                    image.hints.size() * sizeof(uint32_t));
     return FST_OK;
 }
 
-int launch_ranges(const std::vector<LaunchRange> &ranges, const DevDesc *table_dev, const void *src_dev, void *stream)
+int launch_ranges(const TableImage &image, const void *table_dev, const void *src_dev, void *stream)
 {
-    for (const LaunchRange &r : ranges)
-        if (int rc = launch_class_kernels(r.cls, table_dev + r.first, r.count, r.tiles, src_dev, stream)) return rc;
+    const DevDesc *descs = static_cast<const DevDesc *>(table_dev);
+    const uint32_t *hints = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(table_dev) +
+                                                               table_hint_offset(image.descs.size()));
+    for (const LaunchRange &r : image.ranges)
+        if (int rc = launch_class_kernels(r.cls, descs + r.first, hints + r.hint_first, r.tiles, src_dev, stream))
+            return rc;
     return FST_OK;
 }
 
@@ -109,17 +144,16 @@ int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, siz
     if (reinterpret_cast<uintptr_t>(src_dev) % FST_RAW_ALIGN)
         return fail(FST_E_ALIGN, "raw buffer is not %d-byte aligned", FST_RAW_ALIGN);
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
-    if (ws_len < n_pieces * sizeof(DevDesc))
-        return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, n_pieces * sizeof(DevDesc));
 
     std::lock_guard<std::mutex> lock(p->image_mu);
-    std::vector<DevDesc> &image = p->images[group];
-    std::vector<LaunchRange> ranges;
-    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image, ranges)) return rc;
+    TableImage &image = p->images[group];
+    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image)) return rc;
+    if (ws_len < image.blob.size())
+        return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, image.blob.size());
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(ws, image.data(), image.size() * sizeof(DevDesc), hipMemcpyHostToDevice, s);
+    hipError_t e = hipMemcpyAsync(ws, image.blob.data(), image.blob.size(), hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail(FST_E_HIP, "table upload failed: %s", hipGetErrorString(e));
-    return launch_ranges(ranges, static_cast<const DevDesc *>(ws), src_dev, stream);
+    return launch_ranges(image, ws, src_dev, stream);
 }
 
 }  // namespace

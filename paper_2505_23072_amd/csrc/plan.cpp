@@ -106,18 +106,26 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
         if (int rc = push(PATH_ELEM, src0, dst0, row_units, row_units, 1)) return rc;
     } else if (rows == 1) {
         const uint64_t full = row_units / chunk, tail = row_units % chunk;
-        if (full) {
-            // one long row: present it as rows of one tile each so that in-row offsets stay 32-bit
-            if (int rc = push(PATH_VEC, src0, dst0, full, std::min<uint64_t>(full, UINT32_MAX), 1)) return rc;
+        // one long row, in pieces whose chunk indices fit 32 bits
+        for (uint64_t c = 0; c < full; c += VEC_PIECE_MAX_UNITS) {
+            const uint64_t n = std::min(full - c, VEC_PIECE_MAX_UNITS);
+            if (int rc = push(PATH_VEC, src0 + c * chunk * unit_s, dst0 + c * chunk * unit_d, n, 1, 1)) return rc;
             Piece &pc = g.pieces.back();
             pc.units_per_row = 0;       // 0 = a single row of any length
-            pc.src_span = full * chunk * unit_s;
+            pc.src_span = n * chunk * unit_s;
         }
         if (tail)
             if (int rc = push(PATH_ELEM, src0 + full * chunk * unit_s, dst0 + full * chunk * unit_d, tail, tail, 1))
                 return rc;
     } else if (row_units % chunk == 0) {
-        if (int rc = push(PATH_VEC, src0, dst0, rows * (row_units / chunk), row_units / chunk, rows)) return rc;
+        const uint64_t upr = row_units / chunk;
+        if (upr > VEC_PIECE_MAX_UNITS) return fail(FST_E_RANGE, "a row of output %u is too long for one descriptor", oi);
+        const uint64_t rows_per = VEC_PIECE_MAX_UNITS / upr;
+        for (uint64_t r = 0; r < rows; r += rows_per) {
+            const uint64_t nr = std::min(rows - r, rows_per);
+            if (int rc = push(PATH_VEC, src0 + r * o.src_stride, dst0 + r * upr * chunk * unit_d, nr * upr, upr, nr))
+                return rc;
+        }
     } else {
         if (int rc = push(PATH_ELEM, src0, dst0, rows * row_units, row_units, rows)) return rc;
     }
@@ -255,9 +263,13 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap)
     }
     p->max_group_pieces = 0;
     p->total_pieces = 0;
-    for (const Group &g : G) {
+    for (Group &g : G) {
         p->max_group_pieces = std::max(p->max_group_pieces, g.pieces.size());
         p->total_pieces += g.pieces.size();
+        // a launch of k pieces with t_i tiles has ceil(sum t_i / HINT_SPAN) <= sum (t_i / HINT_SPAN + 1) hints
+        g.hint_bound = 0;
+        for (const Piece &pc : g.pieces)
+            g.hint_bound += ceil_div(pc.n_units, pc.path == PATH_VEC ? VEC_TILE_UNITS : ELEM_TILE_UNITS) / HINT_SPAN + 1;
         p->read_bytes += g.read_bytes;
         p->write_bytes += g.write_bytes;
     }
@@ -473,8 +485,11 @@ uint64_t fst_plan_write_bytes(const fst_plan *p) { return p ? p->write_bytes : 0
 size_t fst_plan_workspace_bytes(const fst_plan *p)
 {
     if (!p) return 0;
-    size_t n = std::max<size_t>(p->total_pieces, 1) * sizeof(DevDesc);
-    return (n + 255) / 256 * 256;
+    // room for the tables of all groups side by side (the stager uploads them together); a table
+    // of several groups merged is never larger
+    size_t n = 0;
+    for (const Group &g : p->groups) n += table_bytes(g.pieces.size(), g.hint_bound);
+    return std::max<size_t>(n, 256);
 }
 
 void fst_plan_free(fst_plan *p) { delete p; }

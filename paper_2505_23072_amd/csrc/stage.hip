@@ -127,9 +127,9 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     const double t_start = now_s();
 
     // device tables of every group, uploaded once before any copy is queued
-    std::vector<std::vector<LaunchRange>> ranges(ng);
+    std::vector<TableImage> images(kernels ? ng : 0);
     std::vector<size_t> table_at(ng, 0);
-    std::vector<DevDesc> all;
+    std::vector<uint8_t> all;
     for (size_t g = 0; g < ng; ++g) {
         const Group &gr = p->groups[g];
         if (streamed) {
@@ -144,11 +144,10 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
                         (unsigned long long)(p->raw_base[gr.file] + gr.hi), raw_len);
         }
         if (kernels) {
-            std::vector<DevDesc> img;
-            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, streamed, img, ranges[g]))
+            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, streamed, images[g]))
                 return rc;
-            table_at[g] = all.size();
-            all.insert(all.end(), img.begin(), img.end());
+            table_at[g] = all.size();                       // blobs are whole multiples of 256 bytes
+            all.insert(all.end(), images[g].blob.begin(), images[g].blob.end());
         }
     }
     if (!streamed) {
@@ -157,9 +156,9 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     }
     if (kernels && !all.empty()) {
         if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
-        if (ws_len < all.size() * sizeof(DevDesc))
-            return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, all.size() * sizeof(DevDesc));
-        HIP_TRY(hipMemcpy(ws, all.data(), all.size() * sizeof(DevDesc), hipMemcpyHostToDevice));
+        if (ws_len < all.size())
+            return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, all.size());
+        HIP_TRY(hipMemcpy(ws, all.data(), all.size(), hipMemcpyHostToDevice));
     }
 
     // cut the groups' staged extents into blocks of at most one ring slot
@@ -219,7 +218,7 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
             if (e == hipSuccess) e = hipStreamWaitEvent(s->compute, ready, 0);
             if (e != hipSuccess) { status = fail(FST_E_HIP, "stream hand-over failed: %s", hipGetErrorString(e)); break; }
             const void *src = streamed ? slot_dev[b.group % n_dev_slots] : raw_dev;
-            status = launch_ranges(ranges[b.group], static_cast<const DevDesc *>(ws) + table_at[b.group], src,
+            status = launch_ranges(images[b.group], static_cast<const uint8_t *>(ws) + table_at[b.group], src,
                                    s->compute);
             if (status == FST_OK && streamed) {
                 e = hipEventRecord(s->events[1 + b.group % n_dev_slots], s->compute);
