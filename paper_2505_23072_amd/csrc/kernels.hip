@@ -15,6 +15,8 @@
 // no byte outside the dwords that hold requested bytes is touched.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+
 #include "fst_internal.h"
 
 namespace fst {
@@ -205,15 +207,38 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
     return o;
 }
 
+// A piece's table entry in scalar registers.  The entry is fetched with one 64-byte scalar load:
+// field-by-field loads would each wait for the one before, and that chain is the longest part of
+// a wavefront's life before its own load is in flight.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+struct PieceRegs {
+    u32x16 w;
+    __device__ __forceinline__ uint64_t src_off() const { return w[0] | (uint64_t(w[1]) << 32); }
+    __device__ __forceinline__ uint64_t src_stride() const { return w[2] | (uint64_t(w[3]) << 32); }
+    __device__ __forceinline__ uint64_t dst() const { return w[4] | (uint64_t(w[5]) << 32); }
+    __device__ __forceinline__ uint64_t n_units() const { return w[6] | (uint64_t(w[7]) << 32); }
+    __device__ __forceinline__ uint32_t units_per_row() const { return w[8]; }
+    __device__ __forceinline__ uint32_t tile0() const { return w[9]; }
+    __device__ __forceinline__ uint32_t n_tiles() const { return w[10]; }
+    __device__ __forceinline__ uint32_t div_m() const { return w[11]; }
+    __device__ __forceinline__ uint32_t div_s() const { return w[12]; }
+};
+static_assert(offsetof(DevDesc, src_off) == 0 && offsetof(DevDesc, src_stride) == 8 && offsetof(DevDesc, dst) == 16 &&
+              offsetof(DevDesc, n_units) == 24 && offsetof(DevDesc, units_per_row) == 32 &&
+              offsetof(DevDesc, tile0) == 36 && offsetof(DevDesc, n_tiles) == 40 && offsetof(DevDesc, div_m) == 44 &&
+              offsetof(DevDesc, div_s) == 48, "PieceRegs reads DevDesc by dword position");
+
 // The piece that owns tile `b`: the hint names the piece that holds the first tile of b's span of
 // HINT_SPAN tiles; the owner is that piece or one of the next few (none for a large tensor).
 // Every tile index below the launch's tile count belongs to a piece, so the walk ends.
-__device__ __forceinline__ const DevDesc *find_piece(const DevDesc *__restrict__ descs,
-                                                     const uint32_t *__restrict__ hints, uint32_t b)
+__device__ __forceinline__ PieceRegs find_piece(const DevDesc *__restrict__ descs,
+                                                const uint32_t *__restrict__ hints, uint32_t b)
 {
-    const DevDesc *d = descs + hints[b / HINT_SPAN];
-    while (b - d->tile0 >= d->n_tiles) ++d;
-    return d;
+    const u32x16 *d = reinterpret_cast<const u32x16 *>(descs + hints[b / HINT_SPAN]);
+    PieceRegs p;
+    p.w = *d;
+    while (b - p.tile0() >= p.n_tiles()) p.w = *++d;
+    return p;
 }
 
 // n / d for n < 2^31 with the multiplier the host derived from d (see division_magic).
@@ -225,16 +250,16 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t m, uint32_t s)
 // One chunk per lane: chunk c of the piece (c < n_units) is read at its row/column offset from
 // `src` and written at dst + c*CD.
 template <uint32_t CONV, bool BYTE>
-__device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint32_t c, const DevDesc *d)
+__device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint32_t c, const PieceRegs &d)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
-    const uint32_t upr = d->units_per_row;
+    const uint32_t upr = d.units_per_row();
     const uint8_t *s;
     if (upr == 0) {
         s = src + uint64_t(c) * CS;                                  // one row of any length
     } else {
-        const uint32_t r = fast_div(c, d->div_m, d->div_s);
-        s = src + uint64_t(r) * d->src_stride + uint64_t(c - r * upr) * CS;
+        const uint32_t r = fast_div(c, d.div_m(), d.div_s());
+        s = src + uint64_t(r) * d.src_stride() + uint64_t(c - r * upr) * CS;
     }
     Chunk32 v;
     if (CS == 16) v.lo = load16<BYTE>(s); else v = load32<BYTE>(s);
@@ -260,13 +285,13 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDe
                                                                      const uint8_t *__restrict__ raw)
 {
     const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
-    const DevDesc *d = find_piece(descs, hints, b);
-    const uint32_t t = b - d->tile0;                                    // tile inside the piece
+    const PieceRegs d = find_piece(descs, hints, b);
+    const uint32_t t = b - d.tile0();                                   // tile inside the piece
     const uint32_t c0 = t * VEC_TILE_UNITS;                             // a piece has at most 2^31 chunks
     // only a piece's last tile can be short; decided on 32-bit tile counts
-    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units) - c0 : VEC_TILE_UNITS;
+    const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units()) - c0 : VEC_TILE_UNITS;
     if (threadIdx.x < n)
-        vec_chunk<CONV, BYTE>(raw + d->src_off, reinterpret_cast<uint8_t *>(d->dst), c0 + threadIdx.x, d);
+        vec_chunk<CONV, BYTE>(raw + d.src_off(), reinterpret_cast<uint8_t *>(d.dst()), c0 + threadIdx.x, d);
 }
 
 // Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
@@ -279,27 +304,28 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
     constexpr uint32_t ES = CONV == CONV_COPY ? 1 : (CONV == CONV_F2H || CONV == CONV_F2B) ? 4 : 2;
     constexpr uint32_t ED = CONV == CONV_COPY ? 1 : (CONV == CONV_H2F || CONV == CONV_B2F) ? 4 : 2;
     const uint32_t b = blockIdx.x;
-    const DevDesc *d = find_piece(descs, hints, b);
-    const uint32_t t = b - d->tile0;
+    const PieceRegs d = find_piece(descs, hints, b);
+    const uint32_t t = b - d.tile0();
     const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
-    const uint32_t n = (t + 1 == d->n_tiles) ? uint32_t(d->n_units - e0) : ELEM_TILE_UNITS;
-    const uint32_t upr = d->units_per_row;
+    const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units() - e0) : ELEM_TILE_UNITS;
+    const uint32_t upr = d.units_per_row();
+    const uint64_t stride = d.src_stride();
     const uint64_t row0 = e0 / upr;
     const uint32_t col0 = uint32_t(e0 - row0 * upr);
-    const uint8_t *src = raw + d->src_off + row0 * d->src_stride;
-    uint8_t *dst = reinterpret_cast<uint8_t *>(d->dst) + e0 * ED;
+    const uint8_t *src = raw + d.src_off() + row0 * stride;
+    uint8_t *dst = reinterpret_cast<uint8_t *>(d.dst()) + e0 * ED;
     for (uint32_t i = threadIdx.x; i < n; i += ELEM_BLOCK_THREADS) {
         const uint64_t cc = uint64_t(col0) + i;
         const uint64_t r = cc / upr;
-        const uint8_t *s = src + r * d->src_stride + (cc - r * upr) * ES;
+        const uint8_t *s = src + r * stride + (cc - r * upr) * ES;
         uint32_t v = 0;
 #pragma unroll
         for (uint32_t k = 0; k < ES; ++k) v |= uint32_t(*(const FST_GLOBAL uint8_t *)(s + k)) << (8 * k);
         v = convert_bits<CONV>(v);
-        uint8_t *t = dst + uint64_t(i) * ED;
-        if (ED == 1) *(FST_GLOBAL uint8_t *)(t) = uint8_t(v);
-        else if (ED == 2) *(FST_GLOBAL uint16_t *)(t) = uint16_t(v);
-        else *(FST_GLOBAL uint32_t *)(t) = v;
+        uint8_t *o = dst + uint64_t(i) * ED;
+        if (ED == 1) *(FST_GLOBAL uint8_t *)(o) = uint8_t(v);
+        else if (ED == 2) *(FST_GLOBAL uint16_t *)(o) = uint16_t(v);
+        else *(FST_GLOBAL uint32_t *)(o) = v;
     }
 }
 
