@@ -177,10 +177,102 @@ __device__ __forceinline__ uint32_t narrow_pair(uint32_t packed)       // two 16
     return convert_bits<CONV>(packed & 0xFFFFu) | (convert_bits<CONV>(packed >> 16) << 16);
 }
 
+// ---- the same conversions on the conversion instructions of the vector ALU, for chunks without
+// infinities and NaNs.  For every other input IEEE 754 fixes the result of a round-to-nearest-even
+// conversion bit for bit, and the kernels run with denormals kept and that rounding mode (the
+// defaults of a HIP kernel), so both formulations agree there; the parity tests compare them over
+// all 16-bit inputs and all 2^32 binary32 inputs.  NaN payload handling is a matter of choice, so
+// chunks that hold an all-ones exponent take the integer formulation above.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f32x2 widen_half_pair(uint32_t w)
+{
+    return __builtin_convertvector(__builtin_bit_cast(f16x2, w), f32x2);
+}
+__device__ __forceinline__ f32x2 widen_bfloat_pair(uint32_t w)
+{
+    f32x2 f;
+    f.x = __uint_as_float(w << 16);
+    f.y = __uint_as_float(w & 0xFFFF0000u);
+    return f;
+}
+__device__ __forceinline__ f32x2 float_pair(uint32_t a, uint32_t b)
+{
+    f32x2 f;
+    f.x = __uint_as_float(a);
+    f.y = __uint_as_float(b);
+    return f;
+}
+__device__ __forceinline__ uint32_t narrow_to_bfloat_pair(f32x2 f)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+__device__ __forceinline__ uint32_t narrow_to_half_pair(f32x2 f)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+}
+
+// True when some element of the chunk has an all-ones exponent field.  Adding the field's lowest
+// bit to the masked field carries into the bit above it exactly when the field is all ones; for
+// two 16-bit elements in a word the lower carry stops at bit 15, below the upper element.
+template <uint32_t CONV>
+__device__ __forceinline__ bool chunk_has_inf_or_nan(const Chunk32 &in)
+{
+    constexpr bool WIDE = CONV == CONV_F2H || CONV == CONV_F2B;
+    constexpr uint32_t MASK = WIDE ? 0x7F800000u : CONV == CONV_B2H ? 0x7F807F80u : 0x7C007C00u;
+    constexpr uint32_t LOW = WIDE ? 0x00800000u : CONV == CONV_B2H ? 0x00800080u : 0x04000400u;
+    uint32_t acc = ((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW) | ((in.lo.z & MASK) + LOW) |
+                   ((in.lo.w & MASK) + LOW);
+    if (WIDE)
+        acc |= ((in.hi.x & MASK) + LOW) | ((in.hi.y & MASK) + LOW) | ((in.hi.z & MASK) + LOW) |
+               ((in.hi.w & MASK) + LOW);
+    return (acc & 0x80008000u) != 0;
+}
+
+template <uint32_t CONV>
+__device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
+{
+    Chunk32 o;
+    if (CONV == CONV_H2B) {
+        o.lo.x = narrow_to_bfloat_pair(widen_half_pair(in.lo.x));
+        o.lo.y = narrow_to_bfloat_pair(widen_half_pair(in.lo.y));
+        o.lo.z = narrow_to_bfloat_pair(widen_half_pair(in.lo.z));
+        o.lo.w = narrow_to_bfloat_pair(widen_half_pair(in.lo.w));
+    } else if (CONV == CONV_B2H) {
+        o.lo.x = narrow_to_half_pair(widen_bfloat_pair(in.lo.x));
+        o.lo.y = narrow_to_half_pair(widen_bfloat_pair(in.lo.y));
+        o.lo.z = narrow_to_half_pair(widen_bfloat_pair(in.lo.z));
+        o.lo.w = narrow_to_half_pair(widen_bfloat_pair(in.lo.w));
+    } else if (CONV == CONV_H2F) {
+        const f32x2 a = widen_half_pair(in.lo.x), b = widen_half_pair(in.lo.y);
+        const f32x2 c = widen_half_pair(in.lo.z), d = widen_half_pair(in.lo.w);
+        o.lo.x = __float_as_uint(a.x); o.lo.y = __float_as_uint(a.y);
+        o.lo.z = __float_as_uint(b.x); o.lo.w = __float_as_uint(b.y);
+        o.hi.x = __float_as_uint(c.x); o.hi.y = __float_as_uint(c.y);
+        o.hi.z = __float_as_uint(d.x); o.hi.w = __float_as_uint(d.y);
+    } else if (CONV == CONV_F2H) {
+        o.lo.x = narrow_to_half_pair(float_pair(in.lo.x, in.lo.y));
+        o.lo.y = narrow_to_half_pair(float_pair(in.lo.z, in.lo.w));
+        o.lo.z = narrow_to_half_pair(float_pair(in.hi.x, in.hi.y));
+        o.lo.w = narrow_to_half_pair(float_pair(in.hi.z, in.hi.w));
+    } else if (CONV == CONV_F2B) {
+        o.lo.x = narrow_to_bfloat_pair(float_pair(in.lo.x, in.lo.y));
+        o.lo.y = narrow_to_bfloat_pair(float_pair(in.lo.z, in.lo.w));
+        o.lo.z = narrow_to_bfloat_pair(float_pair(in.hi.x, in.hi.y));
+        o.lo.w = narrow_to_bfloat_pair(float_pair(in.hi.z, in.hi.w));
+    }
+    return o;
+}
+
 // One chunk: 8 elements (or 16 raw bytes) in, converted out.
 template <uint32_t CONV>
 __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
 {
+    // bfloat16 -> binary32 is a shift either way
+    if (CONV != CONV_COPY && CONV != CONV_B2F)
+        if (!chunk_has_inf_or_nan<CONV>(in)) return convert_chunk_finite<CONV>(in);
     Chunk32 o;
     if (CONV == CONV_COPY) {
         o.lo = in.lo;

@@ -46,7 +46,7 @@ def test_random_files(seed):
     _check(got, want, names, reqs, "sparse slots")
 
 
-# several tiles (a tile is 64 KiB of output) and a ragged tail
+# several tiles (a tile is 16 KiB of output) and a ragged tail
 SHAPE = (523, 264)
 
 
@@ -143,6 +143,41 @@ def test_f32_conversions_on_device(dst):
         got, _ = materialize_resident([blob], ["x"], [(dst, -1, 1)])
         want = orc.cast_array(x, "F32", dst).tobytes()
         assert got[0] == want, f"F32->{dst} lead {lead}: {first_diff(got[0], want)}"
+
+
+@pytest.mark.parametrize("dst", ["BF16", "F16"])
+def test_every_binary32_pattern_on_device(dst):
+    """All 2^32 binary32 inputs, in slabs of 2^27, the source one byte off dword alignment in every
+    other slab.  The oracle side runs on a thread pool (its conversion is a plain C loop)."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from synth import writer as w
+    n = 1 << 27
+    workers = 16
+    step = n // workers
+    with ThreadPoolExecutor(workers) as pool:
+        for slab in range(32):
+            lead = slab & 1
+            x = np.arange(slab * n, (slab + 1) * n, dtype=np.uint64).astype(np.uint32)
+            head, _ = w.build_header([("lead", "U8", (lead,), lead), ("x", "F32", (n,), 4 * n)], None, 0)
+            want = pool.map(lambda k: orc.cast_array(x[k * step:(k + 1) * step], "F32", dst), range(workers))
+            size = len(head) + lead + 4 * n
+            raw = device.device_bytes(size + 256)
+            raw[:len(head) + lead].copy_(torch.from_numpy(np.frombuffer(head + bytes(lead), np.uint8).copy()))
+            raw[len(head) + lead:size].copy_(torch.from_numpy(x.view(np.uint8)))
+            plan = B.Plan([B.Header(head, size)], [0], ["x"], [(dst, -1, 1)], 0, 1)
+            bufs, ptrs = device.alloc_outputs(plan)
+            ws = device.device_bytes(plan.workspace_bytes())
+            B.fst_materialize(raw.data_ptr(), size, plan, B.FST_ALL_GROUPS, ptrs, ws.data_ptr(), ws.numel(), 0)
+            torch.cuda.synchronize()
+            got = bufs[0][:2 * n].cpu().numpy().view(np.uint16)
+            want = np.concatenate(list(want))
+            bad = np.nonzero(got != want)[0]
+            assert len(bad) == 0, (f"F32->{dst} slab {slab}: {len(bad)} differ, first input {int(x[bad[0]]):#010x} "
+                                   f"got {int(got[bad[0]]):#06x} want {int(want[bad[0]]):#06x}")
+            plan.close()
+            if slab % 8 == 7:
+                print(f"F32->{dst}: {slab + 1}/32 slabs equal", flush=True)
 
 
 def test_all_ranks_in_one_pass():
