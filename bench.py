@@ -1,8 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the device-side safetensors deserialization path on one MI355X.
 
-Workload: the Llama-7B-shaped synthetic checkpoint (32 layers, hidden 4096, bf16, 13.48 GB in two
-files whose bodies start at byte residues 3 and 8 mod 16), materialized unchanged.
+Default workload: the Llama-7B-shaped synthetic checkpoint (32 layers, hidden 4096, bf16, 13.48 GB
+in two files whose bodies start at byte residues 3 and 8 mod 16), materialized unchanged.  The other
+configurations (`--workload`) run the same legs with their own requests (conversion, one rank's
+partition); checkpoints too large for tmpfs come from the procedural byte source instead of files,
+and one larger than device memory is cut to its first `--layers` layers.
 
 One step = one pass of the hot path with the file bytes already resident in HBM: parse both headers,
 build the load plan, enqueue the materialize kernels for every group, wait.  `value` is
@@ -30,8 +33,40 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "materialize_vec_copy_llama7b_pmc.md")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2505_23072_amd", "csrc", f) for f in ("kernels.hip", "fst_internal.h")]
+
+
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def kernel_sources_digest() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size), or None when
+    there is no summary for this workload or the kernel sources changed after it was taken."""
+    try:
+        text = open(PMC_SUMMARY).read()
+    except OSError:
+        return None
+    fields = {}
+    for line in text.splitlines():
+        if line.startswith("    ") and ":" in line:
+            k, v = line.strip().split(":", 1)
+            fields[k.strip()] = v.strip()
+    if fields.get("kernel_sources_sha256") != kernel_sources_digest():
+        return None
+    v = fields.get(f"traffic_bytes_per_launch[{kernel}]")
+    return int(v) if v else None
 
 
 def main() -> int:
@@ -39,14 +74,17 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama-7b", choices=["llama-7b", "tiny", "llama-13b"])
+    ap.add_argument("--workload", default="llama-7b",
+                    choices=["llama-7b", "tiny", "llama-13b", "llama-70b", "bloom-176b", "falcon-40b"])
+    ap.add_argument("--layers", type=int, default=None,
+                    help="bloom-176b only: keep the first N layers (all 70 need 352 GB resident; default 22)")
     ap.add_argument("--dir", default=None, help="where the synthetic files are written (default: tmpfs)")
     ap.add_argument("--e2e-reps", type=int, default=3)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-baseline budget per leg")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 4 GiB device copy kernel (reference for rocprofv3 --pmc byte counters)")
+                    help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
     ap.add_argument("--slots", type=int, default=16)
     ap.add_argument("--slot-bytes", type=int, default=32 << 20)
@@ -67,21 +105,36 @@ def main() -> int:
 
     dev = device.require_gpu()
     B.lib()
-    spec = specs.CONFIGS[args.workload]()
+    cut = ""
+    if args.workload == "bloom-176b":
+        n_layers = args.layers or 22
+        spec = specs.config5_bloom176b(layers=n_layers)
+        cut = f" (first {n_layers} of 70 layers, embeddings and final norms: what fits resident)" if n_layers < 70 else ""
+    else:
+        spec = specs.CONFIGS[args.workload]()
     t0 = time.time()
     model = ProceduralModel(spec)
+    sizes = list(model.sizes)
+    from_files = sum(sizes) <= (32 << 30)
     base_dir = args.dir or ("/dev/shm" if os.path.isdir("/dev/shm") else tempfile.gettempdir())
-    work = tempfile.mkdtemp(prefix="fst_bench_", dir=base_dir)
+    work = tempfile.mkdtemp(prefix="fst_bench_", dir=base_dir) if from_files else None
     try:
-        paths = model.write_all(work, threads=16)
-        sizes = [os.path.getsize(p) for p in paths]
-        log(f"{spec.name}: {len(paths)} files, {sum(sizes) / 1e9:.2f} GB written to {work} in {time.time() - t0:.1f}s")
+        if from_files:
+            paths = model.write_all(work, threads=16)
+            assert sizes == [os.path.getsize(p) for p in paths]
+            log(f"{spec.name}: {len(paths)} files, {sum(sizes) / 1e9:.2f} GB written to {work} in {time.time() - t0:.1f}s")
+        else:
+            paths = []
+            log(f"{spec.name}: {len(sizes)} files, {sum(sizes) / 1e9:.2f} GB from the procedural source (not stored)")
         names = [t.name for f in spec.files for t in f.tensors]
         reqs = [(t.dst_dtype, t.shard_dim, t.blocks) for f in spec.files for t in f.tensors]
         bases, raw_len = device.file_bases(sizes)
 
         def parse_and_plan(group_bytes):
-            hs = [device.read_header(p)[0] for p in paths]
+            if from_files:
+                hs = [device.read_header(p)[0] for p in paths]
+            else:
+                hs = [B.Header(h, n) for h, n in zip(model.headers, sizes)]
             plan = B.Plan(hs, bases, names, reqs, spec.rank, spec.world)
             plan.set_groups(group_bytes)
             return plan
@@ -93,11 +146,14 @@ def main() -> int:
         rd, wr = plan.read_bytes(), plan.write_bytes()
         log(f"plan: {plan.output_count()} outputs, {plan.group_count()} groups, read {rd / 1e9:.3f} GB, write {wr / 1e9:.3f} GB")
 
-        # ---------------- end-to-end: tmpfs -> pinned ring -> HBM -> tensors
+        # ---------------- end-to-end: tmpfs (or procedural source) -> pinned ring -> HBM -> tensors
         stager = B.Stager(args.slots, args.threads, args.slot_bytes)
         fds = [os.open(p, os.O_RDONLY) for p in paths]
-        fd_arr = (ctypes.c_int * len(fds))(*fds)
-        read_fn, ctx = B.read_fds_fn(), ctypes.addressof(fd_arr)
+        fd_arr = (ctypes.c_int * max(len(fds), 1))(*fds)
+        if from_files:
+            read_fn, ctx = B.read_fds_fn(), ctypes.addressof(fd_arr)
+        else:
+            read_fn, ctx = model.read_fn, model.ctx
 
         def stage(flags):
             return stager.stage_resident(plan, read_fn, ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(),
@@ -132,7 +188,8 @@ def main() -> int:
                 "h2d_gbps_pure": round(staged / t_h2d / 1e9, 2),
                 "h2d_gbps_end_to_end": round(staged / (t_full + t_plan) / 1e9, 2),
                 "reader_threads": args.threads, "ring": f"{args.slots}x{args.slot_bytes >> 20}MiB",
-                "source": "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread",
+                "source": ("procedural byte source (bytes generated into the ring, nothing stored)" if not from_files
+                           else "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread"),
             }
             log("e2e", e2e)
         for fd in fds:
@@ -140,12 +197,13 @@ def main() -> int:
         stager.close()
 
         if args.calibrate_copy:
-            # a plain copy of known size: 4 GiB read + 4 GiB written per dispatch
-            n_cal = 1 << 30
-            a = torch.empty(n_cal, dtype=torch.int32, device=dev).fill_(7)
-            b = torch.empty(n_cal, dtype=torch.int32, device=dev)
+            # a plain device-to-device copy of known size (the runtime's own copy kernel): 4 GiB read
+            # and 4 GiB written per dispatch, the yardstick for the rocprofv3 --pmc byte counters
+            n_cal = 4 << 30
+            a = torch.empty(n_cal, dtype=torch.uint8, device=dev).fill_(7)
+            b = torch.empty(n_cal, dtype=torch.uint8, device=dev)
             for _ in range(3):
-                torch.add(a, 0, out=b)          # one elementwise kernel: reads a, writes b
+                b.copy_(a)
             torch.cuda.synchronize()
             del a, b
 
@@ -180,14 +238,17 @@ def main() -> int:
         ng = plan.group_count()
         groups = [plan.group(g) for g in range(ng)]
         dom = max(range(ng), key=lambda g: groups[g]["read_bytes"] + groups[g]["write_bytes"])
+        # tables uploaded once (fst_prepare), so that the events bracket the kernels alone (fst_launch)
         wss = [device.device_bytes(plan.workspace_bytes(), dev) for _ in range(ng)]
+        for g in range(ng):
+            B.fst_prepare(plan, g, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, wss[g].data_ptr(), wss[g].numel(), sp)
         per_group_ms = [[] for _ in range(ng)]
         for it in range(args.warmup + args.steps):
             evs = [torch.cuda.Event(enable_timing=True) for _ in range(ng + 1)]
             with torch.cuda.stream(stream):
                 evs[0].record(stream)
                 for g in range(ng):
-                    B.fst_materialize(raw.data_ptr(), raw_len, plan, g, ptrs, wss[g].data_ptr(), wss[g].numel(), sp)
+                    B.fst_launch(plan, g, raw.data_ptr(), raw_len, sp)
                     evs[g + 1].record(stream)
             torch.cuda.synchronize()
             if it >= args.warmup:
@@ -197,10 +258,15 @@ def main() -> int:
         dom_bytes = groups[dom]["read_bytes"] + groups[dom]["write_bytes"]
         achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
         align = (model.headers[groups[dom]["file"]].__len__()) % 16
+        if all(r == (None, -1, 1) for r in reqs):
+            kernel = "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>"
+        else:
+            kernel = "all materialize kernels of the largest file (one fst_materialize call: conversions and partitions included)"
         roofline = {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-            "kernel": "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": recorded_traffic(kernel) if args.workload == "llama-7b" else None,
+            "kernel": kernel,
             "launch_bytes": dom_bytes, "launch_ms_avg": round(dom_ms, 4), "launch_ms_min": round(float(np.min(per_group_ms[dom])), 4),
             "all_launches": [{"file": groups[g]["file"], "source_residue_mod16": len(model.headers[groups[g]["file"]]) % 16,
                               "bytes": groups[g]["read_bytes"] + groups[g]["write_bytes"],
@@ -213,15 +279,15 @@ def main() -> int:
         # ---------------- CPU baseline: the oracle on a bounded sample of the same files
         cpu = None
         if not args.no_cpu:
-            cpu = cpu_baseline(paths, spec, args.cpu_seconds)
+            cpu = cpu_baseline(model, spec, args.cpu_seconds)
 
         out = {
             "metric": "materialize GB/s (% of HBM peak) + end-to-end file->tensors seconds, 1 GPU",
             "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "u8", "data": "synthetic",
-            "config": {"workload": f"{spec.name}: {spec.n_tensors} tensors, {len(paths)} files, {sum(sizes)} bytes, "
-                                   "bf16 N(0,0.02), materialize all, no cast, no slice",
+            "dtype": "u8" if all(r[0] is None for r in reqs) else "u16", "data": "synthetic",
+            "config": {"workload": f"{spec.name}{cut}: {spec.n_tensors} tensors, {len(sizes)} files, {sum(sizes)} bytes, "
+                                   f"N(0,0.02), {describe_requests(spec)}",
                        "bytes_read": rd, "bytes_written": wr,
                        "step": "parse headers + plan + materialize kernels, raw bytes resident in HBM"},
             "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
@@ -234,19 +300,35 @@ def main() -> int:
         print(json.dumps(out), flush=True)
         return 0
     finally:
-        shutil.rmtree(work, ignore_errors=True)
+        if work:
+            shutil.rmtree(work, ignore_errors=True)
 
 
-def cpu_baseline(paths, spec, budget_s):
+def describe_requests(spec) -> str:
+    ts = [t for f in spec.files for t in f.tensors]
+    stored = sorted({t.dtype for t in ts})
+    conv = sorted({f"{t.dtype}->{t.dst_dtype}" for t in ts if t.dst_dtype and t.dst_dtype != t.dtype})
+    d0 = sum(1 for t in ts if t.shard_dim == 0 and t.blocks == 1)
+    d0b = sum(1 for t in ts if t.shard_dim == 0 and t.blocks > 1)
+    d1 = sum(1 for t in ts if t.shard_dim == 1)
+    parts = ["stored " + "/".join(stored), "cast " + ", ".join(conv) if conv else "no cast"]
+    if spec.world > 1:
+        parts.append(f"rank {spec.rank} of {spec.world}: {d0} tensors split on dim 0, {d0b} on dim 0 in blocks, "
+                     f"{d1} on dim 1, {len(ts) - d0 - d0b - d1} whole")
+    else:
+        parts.append("materialize all, no slice")
+    return ", ".join(parts)
+
+
+def cpu_baseline(model, spec, budget_s):
     """The scalar oracle, as it is, over tensors of the first file in order until the time budget is used:
-    once on one thread, once fanned out over all host cores."""
+    once on one thread, once fanned out over all host cores.  The stored bytes come from the same byte
+    source as the files (regenerated per tensor, untimed)."""
     import numpy as np
 
     from oracle import oracle as orc
 
-    blob = np.memmap(paths[0], dtype=np.uint8, mode="r")
-    n = orc.header_len(bytes(blob[:8]))
-    table = orc.parse(bytes(blob[:8 + n]), blob.size)
+    table = orc.parse(model.headers[0], model.sizes[0])
     req = {t.name: t for t in spec.files[0].tensors}
     cores = len(os.sched_getaffinity(0))
 
@@ -254,7 +336,7 @@ def cpu_baseline(paths, spec, budget_s):
         js = []
         for t in tensors:
             r = req[t.name]
-            stored = np.array(blob[table.body_off + t.begin: table.body_off + t.end])      # into RAM, untimed
+            stored = model.read(0, table.body_off + t.begin, t.end - t.begin)      # into RAM, untimed
             _, nb = orc.result_info(t.dtype, t.shape, r.dst_dtype, r.shard_dim, r.blocks, spec.rank, spec.world)
             js.append(dict(stored=stored, dtype=t.dtype, shape=t.shape, dst_dtype=r.dst_dtype, shard_dim=r.shard_dim,
                            blocks=r.blocks, rank=spec.rank, world=spec.world, out=np.empty(nb, np.uint8)))

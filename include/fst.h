@@ -263,6 +263,28 @@ int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *
                          void *const *out_ptrs, void *dev_workspace, size_t workspace_len,
                          void *stream);
 
+/*
+ * The two halves of fst_materialize, for callers that launch a group more than once or want the
+ * launch apart from the table upload (timing the kernels alone; a ring of device slots that all
+ * hold the same group layout).
+ *
+ * fst_prepare builds the table of `group` (or FST_ALL_GROUPS, resident layout only) for the given
+ * layout and output pointers, checks every source range against src_len exactly as
+ * fst_materialize does, and enqueues the upload into dev_workspace on `stream`.  The workspace
+ * then belongs to that group until it is prepared again or the groups are re-cut.
+ *
+ * fst_launch enqueues only the kernels of a prepared group on `stream`: no copy, no allocation.
+ * The stream must be the one given to fst_prepare or be ordered after it.  src_dev may differ
+ * from call to call (FST_RAW_ALIGN-aligned, device) as long as it holds the same layout and
+ * src_len is at least the length the group was prepared with (FST_E_RANGE otherwise); a group
+ * that was not prepared is FST_E_ARG.  A group without work is a successful no-op in both.
+ */
+#define FST_LAYOUT_RESIDENT 0
+#define FST_LAYOUT_SLOT 1
+int fst_prepare(const fst_plan *p, size_t group, int32_t layout, size_t src_len, void *const *out_ptrs,
+                void *dev_workspace, size_t workspace_len, void *stream);
+int fst_launch(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream);
+
 /* ---------------------------------------------------------------- staging (Section III-A)
  *
  * The fallback path of the paper: file bytes are read into a small DMA-able (pinned) bounce

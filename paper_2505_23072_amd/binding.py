@@ -105,6 +105,8 @@ _SIGNATURES = {
                                 c_void_p]),
     "fst_materialize_slot": (c_int, [c_void_p, c_size_t, c_void_p, c_size_t, POINTER(c_void_p), c_void_p,
                                      c_size_t, c_void_p]),
+    "fst_prepare": (c_int, [c_void_p, c_size_t, c_int32, c_size_t, POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
+    "fst_launch": (c_int, [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
     "fst_stager_create": (c_int, [POINTER(fst_stager_config), POINTER(c_void_p)]),
     "fst_stager_destroy": (None, [c_void_p]),
     "fst_read_fds": (c_int, [c_void_p, c_int32, c_uint64, c_void_p, c_uint64]),
@@ -329,6 +331,19 @@ def fst_materialize_slot(slot_ptr: int, slot_len: int, plan: Plan, group: int, o
                          workspace_ptr: int, workspace_len: int, stream: int = 0) -> None:
     _check(lib().fst_materialize_slot(c_void_p(slot_ptr), slot_len, plan.handle, group, _ptr_array(out_ptrs),
                                       c_void_p(workspace_ptr), workspace_len, c_void_p(stream)))
+
+
+FST_LAYOUT_RESIDENT, FST_LAYOUT_SLOT = 0, 1
+
+
+def fst_prepare(plan: Plan, group: int, layout: int, src_len: int, out_ptrs: Sequence[int], workspace_ptr: int,
+                workspace_len: int, stream: int = 0) -> None:
+    _check(lib().fst_prepare(plan.handle, group, layout, src_len, _ptr_array(out_ptrs), c_void_p(workspace_ptr),
+                             workspace_len, c_void_p(stream)))
+
+
+def fst_launch(plan: Plan, group: int, src_ptr: int, src_len: int, stream: int = 0) -> None:
+    _check(lib().fst_launch(plan.handle, group, c_void_p(src_ptr), src_len, c_void_p(stream)))
 
 
 class Stager:

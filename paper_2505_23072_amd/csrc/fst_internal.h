@@ -142,6 +142,10 @@ struct TableImage {
     std::vector<uint32_t> hints;      // per launch: for tile HINT_SPAN*k, the piece (from the launch's first) holding it
     std::vector<LaunchRange> ranges;
     std::vector<uint8_t> blob;        // what is copied to the device: descs, then hints at table_hint_offset
+    // set by fst_prepare: where the blob was uploaded and the source length it was checked against
+    const void *dev = nullptr;
+    size_t src_len = 0;
+    bool prepared = false;
 };
 // Bytes a table occupies in the workspace: pieces first, hints after them on a 256-byte boundary.
 inline size_t table_hint_offset(size_t n_descs) { return (n_descs * sizeof(DevDesc) + 255) / 256 * 256; }

@@ -123,13 +123,10 @@ int launch_ranges(const TableImage &image, const void *table_dev, const void *sr
 
 namespace {
 
-int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
-                     void *ws, size_t ws_len, void *stream, bool slot)
+int group_range(const fst_plan *p, size_t group, bool slot, size_t &g0, size_t &g1)
 {
-    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
-    size_t g0, g1;
     if (group == FST_ALL_GROUPS) {
-        if (slot) return fail(FST_E_ARG, "fst_materialize_slot takes one group");
+        if (slot) return fail(FST_E_ARG, "the slot layout takes one group at a time");
         g0 = 0;
         g1 = p->groups.size();
     } else {
@@ -137,23 +134,51 @@ int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, siz
         g0 = group;
         g1 = group + 1;
     }
+    return FST_OK;
+}
+
+// Builds the group's table and enqueues its upload into the workspace.  Caller holds image_mu.
+int prepare_locked(const fst_plan *p, size_t group, bool slot, size_t src_len, void *const *out_ptrs, void *ws,
+                   size_t ws_len, void *stream)
+{
+    size_t g0, g1;
+    if (int rc = group_range(p, group, slot, g0, g1)) return rc;
+    TableImage &image = p->images[group];
+    image.dev = nullptr;
     size_t n_pieces = 0;
     for (size_t g = g0; g < g1; ++g) n_pieces += p->groups[g].pieces.size();
-    if (n_pieces == 0) return FST_OK;
-    if (!src_dev) return fail(FST_E_ARG, "fst_materialize: raw buffer is NULL");
-    if (reinterpret_cast<uintptr_t>(src_dev) % FST_RAW_ALIGN)
-        return fail(FST_E_ALIGN, "raw buffer is not %d-byte aligned", FST_RAW_ALIGN);
+    if (n_pieces == 0) {                       // nothing to launch: prepared, with an empty table
+        image = TableImage{};
+        image.prepared = true;
+        return FST_OK;
+    }
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
-
-    std::lock_guard<std::mutex> lock(p->image_mu);
-    TableImage &image = p->images[group];
     if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image)) return rc;
     if (ws_len < image.blob.size())
         return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, image.blob.size());
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(ws, image.blob.data(), image.blob.size(), hipMemcpyHostToDevice, s);
+    hipError_t e = hipMemcpyAsync(ws, image.blob.data(), image.blob.size(), hipMemcpyHostToDevice,
+                                  static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(FST_E_HIP, "table upload failed: %s", hipGetErrorString(e));
-    return launch_ranges(image, ws, src_dev, stream);
+    image.dev = ws;
+    image.src_len = src_len;
+    image.prepared = true;
+    return FST_OK;
+}
+
+// Enqueues the kernels of a prepared group.  Caller holds image_mu.
+int launch_locked(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream)
+{
+    auto it = p->images.find(group);
+    if (it == p->images.end() || !it->second.prepared)
+        return fail(FST_E_ARG, "group %zu has no uploaded table: call fst_prepare first", group);
+    const TableImage &image = it->second;
+    if (image.ranges.empty()) return FST_OK;
+    if (!src_dev) return fail(FST_E_ARG, "source buffer is NULL");
+    if (reinterpret_cast<uintptr_t>(src_dev) % FST_RAW_ALIGN)
+        return fail(FST_E_ALIGN, "source buffer is not %d-byte aligned", FST_RAW_ALIGN);
+    if (src_len < image.src_len)
+        return fail(FST_E_RANGE, "source buffer has %zu bytes, the table was prepared for %zu", src_len, image.src_len);
+    return launch_ranges(image, image.dev, src_dev, stream);
 }
 
 }  // namespace
@@ -161,30 +186,63 @@ int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, siz
 
 using namespace fst;
 
+#define FST_GUARD(expr)                                              \
+    try { return (expr); }                                           \
+    catch (const std::bad_alloc &) { return fail(FST_E_NOMEM, "out of memory"); } \
+    catch (...) { return fail(FST_E_ARG, "unexpected internal error"); }
+
+namespace {
+
+int prepare_impl(const fst_plan *p, size_t group, int32_t layout, size_t src_len, void *const *out_ptrs, void *ws,
+                 size_t ws_len, void *stream)
+{
+    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_prepare: NULL argument");
+    if (layout != FST_LAYOUT_RESIDENT && layout != FST_LAYOUT_SLOT) return fail(FST_E_ARG, "fst_prepare: unknown layout %d", layout);
+    std::lock_guard<std::mutex> lock(p->image_mu);
+    return prepare_locked(p, group, layout == FST_LAYOUT_SLOT, src_len, out_ptrs, ws, ws_len, stream);
+}
+
+int launch_impl(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream)
+{
+    if (!p) return fail(FST_E_ARG, "fst_launch: plan is NULL");
+    std::lock_guard<std::mutex> lock(p->image_mu);
+    return launch_locked(p, group, src_dev, src_len, stream);
+}
+
+int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
+                     void *ws, size_t ws_len, void *stream, bool slot)
+{
+    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
+    std::lock_guard<std::mutex> lock(p->image_mu);
+    if (int rc = prepare_locked(p, group, slot, src_len, out_ptrs, ws, ws_len, stream)) return rc;
+    return launch_locked(p, group, src_dev, src_len, stream);
+}
+
+}  // namespace
+
 extern "C" {
+
+int fst_prepare(const fst_plan *p, size_t group, int32_t layout, size_t src_len, void *const *out_ptrs,
+                void *dev_workspace, size_t workspace_len, void *stream)
+{
+    FST_GUARD(prepare_impl(p, group, layout, src_len, out_ptrs, dev_workspace, workspace_len, stream));
+}
+
+int fst_launch(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream)
+{
+    FST_GUARD(launch_impl(p, group, src_dev, src_len, stream));
+}
 
 int fst_materialize(const void *raw_dev, size_t raw_len, const fst_plan *p, size_t group, void *const *out_ptrs,
                     void *dev_workspace, size_t workspace_len, void *stream)
 {
-    try {
-        return materialize_impl(raw_dev, raw_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, false);
-    } catch (const std::bad_alloc &) {
-        return fail(FST_E_NOMEM, "out of memory");
-    } catch (...) {
-        return fail(FST_E_ARG, "unexpected internal error");
-    }
+    FST_GUARD(materialize_impl(raw_dev, raw_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, false));
 }
 
 int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *p, size_t group,
                          void *const *out_ptrs, void *dev_workspace, size_t workspace_len, void *stream)
 {
-    try {
-        return materialize_impl(slot_dev, slot_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, true);
-    } catch (const std::bad_alloc &) {
-        return fail(FST_E_NOMEM, "out of memory");
-    } catch (...) {
-        return fail(FST_E_ARG, "unexpected internal error");
-    }
+    FST_GUARD(materialize_impl(slot_dev, slot_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, true));
 }
 
 }  // extern "C"

@@ -213,6 +213,49 @@ def test_on_a_side_stream_and_empty_plan():
     got, plan = materialize_resident([e], ["e", "f"], [(None, -1, 1), ("F32", -1, 1)])
     assert got == [b"", b""] and plan.group_count() == 0
 
+def test_prepare_once_launch_on_two_source_buffers():
+    """The table is uploaded once; the kernels are then launched on two raw buffers of the same layout
+    and different content, and once more per group after re-preparing group by group."""
+    rng = np.random.default_rng(9)
+    ts = [("pad", "U8", (3,), bytes(3)), ("w", "BF16", (520, 264), None), ("h", "F16", (264, 520), None),
+          ("v", "F32", (1031,), None)]
+    blobs = []
+    for k in range(2):
+        full = [(n, d, s, b if b is not None else random_bits(rng, d, s).tobytes()) for n, d, s, b in ts]
+        blobs.append(writer.write_file(None, full, None, 5))
+    names, reqs = ["w", "w", "h", "h", "v"], [(None, 0, 1), ("F16", 1, 1), ("F32", 0, 2), ("BF16", 1, 1), ("BF16", -1, 1)]
+    world, rank = 4, 2
+    hs = headers_of(blobs[:1])
+    plan = B.Plan(hs, [0], names, reqs, rank, world)
+    raws = [upload_resident([b]) for b in blobs]
+    raw_len = raws[0][2]
+    bufs, ptrs = device.alloc_outputs(plan)
+    ws = device.device_bytes(plan.workspace_bytes())
+    with pytest.raises(B.FstError) as e:
+        B.fst_launch(plan, B.FST_ALL_GROUPS, raws[0][0].data_ptr(), raw_len, 0)
+    assert e.value.name == "FST_E_ARG"
+    B.fst_prepare(plan, B.FST_ALL_GROUPS, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, ws.data_ptr(), ws.numel(), 0)
+    with pytest.raises(B.FstError) as e:
+        B.fst_launch(plan, B.FST_ALL_GROUPS, raws[0][0].data_ptr(), raw_len - 4, 0)
+    assert e.value.name == "FST_E_RANGE"
+    for k in (0, 1, 0):
+        for b in bufs:
+            b.fill_(0xC3)
+        B.fst_launch(plan, B.FST_ALL_GROUPS, raws[k][0].data_ptr(), raw_len, 0)
+        from util_gpu import fetch
+        _check(fetch(bufs, plan), oracle_outputs([blobs[k]], names, reqs, rank, world), names, reqs, f"buffer {k}")
+    # cut into small groups: each group prepared into its own part of a larger workspace, then launched
+    ng = plan.set_groups(16384)
+    assert ng > 3
+    wss = [device.device_bytes(plan.workspace_bytes()) for _ in range(ng)]
+    for b in bufs:
+        b.fill_(0x3C)
+    for g in range(ng):
+        B.fst_prepare(plan, g, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, wss[g].data_ptr(), wss[g].numel(), 0)
+    for g in range(ng):
+        B.fst_launch(plan, g, raws[1][0].data_ptr(), raw_len, 0)
+    _check(fetch(bufs, plan), oracle_outputs([blobs[1]], names, reqs, rank, world), names, reqs, "per group")
+
 
 def test_operand_checks_reject_before_any_launch():
     rng = np.random.default_rng(4)

@@ -179,6 +179,25 @@ def test_plan_errors():
         p.group(2)
     with pytest.raises(B.FstError):
         p.descriptor(99)
+    # the operand checks of the launch half come before any GPU call
+    with pytest.raises(B.FstError) as e:
+        B.fst_launch(p, 0, 4096, 1 << 20, 0)            # group 0 was never prepared
+    assert e.value.name == "FST_E_ARG"
+    with pytest.raises(B.FstError) as e:
+        B.fst_prepare(p, 0, 7, 1 << 20, [256, 256, 256], 256, 1 << 20, 0)     # unknown layout
+    assert e.value.name == "FST_E_ARG"
+    with pytest.raises(B.FstError) as e:
+        B.fst_prepare(p, 5, B.FST_LAYOUT_RESIDENT, 1 << 20, [256, 256, 256], 256, 1 << 20, 0)
+    assert e.value.name == "FST_E_RANGE"
+    with pytest.raises(B.FstError) as e:
+        B.fst_prepare(p, B.FST_ALL_GROUPS, B.FST_LAYOUT_SLOT, 1 << 20, [256, 256, 256], 256, 1 << 20, 0)
+    assert e.value.name == "FST_E_ARG"
+    with pytest.raises(B.FstError) as e:
+        B.fst_prepare(p, 0, B.FST_LAYOUT_RESIDENT, 1 << 20, [256, 256, 256], 264, 1 << 20, 0)   # workspace alignment
+    assert e.value.name == "FST_E_ALIGN"
+    with pytest.raises(B.FstError) as e:
+        B.fst_prepare(p, 0, B.FST_LAYOUT_RESIDENT, 64, [256, 256, 256], 256, 1 << 20, 0)        # source too short
+    assert e.value.name == "FST_E_RANGE"
 
 
 def test_uniform_plan_matches_per_name_requests():

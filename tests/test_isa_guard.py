@@ -44,10 +44,9 @@ def scc_findings(asm_text):
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not installed")
 def test_no_scc_consumer_without_producer(tmp_path):
     out = tmp_path / "kernels.s"
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
-                           "-Xclang", "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"),
-                           "-I", os.path.join(ROOT, "paper_2505_23072_amd", "csrc"), "-S", "--cuda-device-only",
-                           "-o", str(out), os.path.join(ROOT, "paper_2505_23072_amd", "csrc", "kernels.hip")],
+    from paper_2505_23072_amd.build import DEVICE_FLAGS
+    subprocess.check_call([HIPCC] + DEVICE_FLAGS + ["-S", "--cuda-device-only", "-o", str(out),
+                                                    os.path.join(ROOT, "paper_2505_23072_amd", "csrc", "kernels.hip")],
                           stderr=subprocess.DEVNULL)
     text = out.read_text()
     assert "materialize_vec" in text and "global_load_dwordx4" in text
