@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
+    ap.add_argument("--min-gap", type=int, default=None,
+                    help="end-to-end leg: do not stage unread file ranges longer than this many bytes "
+                         "(default: stage each group from its first to its last needed byte)")
     ap.add_argument("--slots", type=int, default=16)
     ap.add_argument("--slot-bytes", type=int, default=32 << 20)
     ap.add_argument("--threads", type=int, default=12)
@@ -130,16 +133,16 @@ def main() -> int:
         reqs = [(t.dst_dtype, t.shard_dim, t.blocks) for f in spec.files for t in f.tensors]
         bases, raw_len = device.file_bases(sizes)
 
-        def parse_and_plan(group_bytes):
+        def parse_and_plan(group_bytes, min_gap=None):
             if from_files:
                 hs = [device.read_header(p)[0] for p in paths]
             else:
                 hs = [B.Header(h, n) for h, n in zip(model.headers, sizes)]
             plan = B.Plan(hs, bases, names, reqs, spec.rank, spec.world)
-            plan.set_groups(group_bytes)
+            plan.set_groups(group_bytes, min_gap)
             return plan
 
-        plan = parse_and_plan(args.group_bytes)
+        plan = parse_and_plan(args.group_bytes, args.min_gap)
         raw = device.device_bytes(raw_len, dev)
         ws = device.device_bytes(plan.workspace_bytes(), dev)
         bufs, ptrs = device.alloc_outputs(plan, dev)
@@ -174,7 +177,7 @@ def main() -> int:
             t_h2d, _ = best(B.FST_STAGE_NO_KERNELS | B.FST_STAGE_NO_READ)
             # the end-to-end figure includes header parsing and planning
             t = time.perf_counter()
-            p2 = parse_and_plan(args.group_bytes)
+            p2 = parse_and_plan(args.group_bytes, args.min_gap)
             t_plan = time.perf_counter() - t
             p2.close()
             staged = s_full["staged_bytes"]
@@ -188,6 +191,7 @@ def main() -> int:
                 "h2d_gbps_pure": round(staged / t_h2d / 1e9, 2),
                 "h2d_gbps_end_to_end": round(staged / (t_full + t_plan) / 1e9, 2),
                 "reader_threads": args.threads, "ring": f"{args.slots}x{args.slot_bytes >> 20}MiB",
+                "staging": "whole groups" if args.min_gap is None else f"only the extents read (gaps > {args.min_gap} B skipped)",
                 "source": ("procedural byte source (bytes generated into the ring, nothing stored)" if not from_files
                            else "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread"),
             }

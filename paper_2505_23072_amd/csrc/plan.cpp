@@ -225,6 +225,18 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap)
             const uint64_t row_bytes = o.row_elems * es_s;
             const uint64_t s_lo = o.src_file_off;
             const uint64_t s_hi = s_lo + (o.n_rows - 1) * o.src_stride + row_bytes;
+            // sparse staging: rows that lie further apart than min_gap (the blocks of a fused
+            // matrix) are staged, and worked on, one by one, so the bytes between them stay out
+            if (min_gap != UINT64_MAX && o.n_rows > 1 && o.src_stride - row_bytes > min_gap && row_bytes <= budget) {
+                for (uint64_t r = 0; r < o.n_rows; ++r) {
+                    const uint64_t c_lo = s_lo + r * o.src_stride, c_hi = c_lo + row_bytes;
+                    if (open && max_bytes && space_with(G.back(), c_lo, c_hi, min_gap) > max_bytes) finish();
+                    if (!open) start();
+                    add_range(G.back(), c_lo, c_hi, min_gap);
+                    if (int rc = add_work(p, G.back(), oi, r, r + 1, 0, 0)) return rc;
+                }
+                continue;
+            }
             if (s_hi - s_lo <= budget) {
                 if (open && max_bytes && space_with(G.back(), s_lo, s_hi, min_gap) > max_bytes) finish();
                 if (!open) start();

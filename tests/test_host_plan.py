@@ -141,6 +141,40 @@ def test_plan_geometry_of_named_cases():
     assert p1.descriptor(0)["n_rows"] == 1 and p1.descriptor(0)["row_elems"] == 64 * 48
 
 
+def test_sparse_staging_leaves_out_what_no_request_reads():
+    """Section III-B warns against many small scattered reads, so only gaps above a threshold are skipped:
+    a blocked (fused QKV) share stages its three runs and not the rows between them, a column share of a
+    matrix (gaps of a row each) is staged whole unless the threshold is below the row gap."""
+    from synth import writer
+    qkv = np.arange(3 * 64 * 32, dtype=np.uint16)           # [192, 32]: three blocks of 64 rows
+    o = np.arange(64 * 256, dtype=np.uint16)                 # [64, 256]
+    blob = writer.write_file(None, [("qkv", "F16", (192, 32), qkv.tobytes()), ("o", "F16", (64, 256), o.tobytes())],
+                             None, 9)
+    h = _headers([blob])
+    plan = B.Plan(h, [0], ["qkv", "o"], [(None, 0, 3), (None, 1, 1)], rank=2, world=8)
+    body = len(blob) - 2 * (len(qkv) + len(o))
+    run = 8 * 32 * 2                                         # 8 rows of a block: 512 bytes, blocks 4096 bytes apart
+    ng = plan.set_groups(0, 1024)                            # skip gaps above 1 KiB
+    ex = [e for g in range(ng) for e in plan.group(g)["extents"]]
+    want = [(body + b * 4096 + 2 * run, body + b * 4096 + 3 * run) for b in range(3)]
+    # o: rank 2's columns 64..95 of every row: from the first to the last needed byte (gaps of 448 bytes stay in)
+    o0 = body + 2 * len(qkv)
+    want.append((o0 + 2 * 64, o0 + 63 * 512 + 3 * 64))
+    assert [(lo, hi) for lo, hi, _ in ex] == want
+    got = _interpret(plan, [blob])
+    assert np.frombuffer(got[0], np.uint16).tolist() == np.concatenate(
+        [qkv.reshape(3, 64, 32)[b, 16:24].ravel() for b in range(3)]).tolist()
+    assert np.frombuffer(got[1], np.uint16).tolist() == o.reshape(64, 256)[:, 64:96].ravel().tolist()
+    # threshold below the row gap: every row segment of o is its own extent
+    ng = plan.set_groups(0, 100)
+    ex = [e for g in range(ng) for e in plan.group(g)["extents"]]
+    assert len(ex) == 3 + 64 and sum(hi - lo for lo, hi, _ in ex) == plan.read_bytes() == 3 * run + 64 * 64
+    assert _interpret(plan, [blob]) == got
+    # no threshold: one extent per group again, from the first to the last byte read
+    ng = plan.set_groups(0)
+    assert [len(plan.group(g)["extents"]) for g in range(ng)] == [1] * ng
+
+
 def test_plan_errors():
     from synth import writer
     a = np.zeros(24, np.uint16).tobytes()
