@@ -37,9 +37,12 @@ struct fst_header {
 namespace fst {
 
 // How a descriptor's rows are moved.  The vector path moves whole chunks (16 bytes when nothing
-// is converted, 8 elements otherwise); the element path moves single elements and serves ragged
-// tails and rows whose byte length is not a whole number of chunks.
-enum Path : uint32_t { PATH_VEC = 0, PATH_ELEM = 1 };
+// is converted, 8 elements otherwise) of rows that are a whole number of chunks.  The spliced path
+// serves rows that are not: its chunks are cut from the output stream, so a chunk may take its
+// first units from the end of one row and the rest from the start of the next.  The element path
+// moves single elements: tails shorter than a chunk, rows shorter than a chunk, and pieces whose
+// first output byte is not 16-byte aligned.
+enum Path : uint32_t { PATH_VEC = 0, PATH_ELEM = 1, PATH_SPLICE = 2 };
 
 // Conversion kinds (Section III-B).  COPY moves bytes and ignores the element type.
 enum Conv : uint32_t { CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CONV_F2H, CONV_F2B, CONV_COUNT };
@@ -49,8 +52,9 @@ struct DevDesc {
     uint64_t src_off;        // byte offset of row 0 from the source pointer of the launch
     uint64_t src_stride;     // bytes between rows
     uint64_t dst;            // device address of the first output byte of this piece
-    uint64_t n_units;        // VEC: chunks in total (rows * units_per_row); ELEM: elements
-    uint32_t units_per_row;  // VEC: chunks per row (0 = one row of any length); ELEM: elements per row
+    uint64_t n_units;        // VEC: chunks in total (rows * units_per_row); SPLICE: chunks; ELEM: elements
+    uint32_t units_per_row;  // VEC: chunks per row (0 = one row of any length); SPLICE, ELEM: elements per row
+                             //   (bytes per row when nothing is converted)
     uint32_t tile0;          // index of this piece's first tile inside its launch
     uint32_t n_tiles;
     uint32_t div_m;          // division by units_per_row as a multiplication: see fast_div
@@ -100,11 +104,13 @@ struct Output {
     uint64_t tensor_begin = 0;   // file offset of the stored tensor (for ordering)
 };
 
-// Launch classes: (conv, byte-aligned?) for the vector path, then one class for the element path.
-constexpr uint32_t N_CLASSES = CONV_COUNT * 2 + CONV_COUNT;
+// Launch classes: (conv, byte-aligned?) for the vector path, then one class per conversion for the
+// element path and for the spliced path.
+constexpr uint32_t N_CLASSES = CONV_COUNT * 4;
 inline uint32_t launch_class(const Piece &p)
 {
-    return p.path == PATH_VEC ? p.conv * 2 + (p.dword_aligned ? 0 : 1) : CONV_COUNT * 2 + p.conv;
+    if (p.path == PATH_VEC) return p.conv * 2 + (p.dword_aligned ? 0 : 1);
+    return CONV_COUNT * (p.path == PATH_ELEM ? 2 : 3) + p.conv;
 }
 
 // Geometry of the kernels, fixed at compile time and needed by the planner to count tiles.
@@ -117,6 +123,7 @@ constexpr uint32_t VEC_UNROLL = 1;                       // chunks per thread
 constexpr uint32_t VEC_TILE_UNITS = VEC_BLOCK_THREADS * VEC_UNROLL;           // chunks per tile
 constexpr uint32_t ELEM_BLOCK_THREADS = 256;
 constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 // elements per tile
+inline uint32_t tile_units(uint32_t path) { return path == PATH_ELEM ? ELEM_TILE_UNITS : VEC_TILE_UNITS; }
 // Workgroups are dealt to the 8 XCDs round-robin.  The tile index is permuted so that each XCD
 // works on runs of XCD_RUN consecutive tiles (1 MiB of output), which measured faster than both
 // tile-by-tile interleaving and giving each XCD one contiguous eighth.
@@ -127,6 +134,8 @@ constexpr uint32_t XCD_RUN = 64;
 constexpr uint32_t HINT_SPAN = 64;
 // Vector pieces are cut so that chunk indices inside a piece fit 32 bits.
 constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;
+// Spliced pieces are cut so that element indices inside a piece stay below 2^31.
+constexpr uint64_t SPLICE_PIECE_MAX_UNITS = (1ull << 31) - 64;
 
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
 uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)

@@ -386,6 +386,73 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDe
         vec_chunk<CONV, BYTE>(raw + d.src_off(), reinterpret_cast<uint8_t *>(d.dst()), c0 + threadIdx.x, d);
 }
 
+// Bytes [0, kb) of `a` followed by bytes [kb, ...) of `b`, word by word (kb in 1 .. size-1).
+__device__ __forceinline__ uint32_t splice_word(uint32_t a, uint32_t b, int32_t kb, int32_t word)
+{
+    const int32_t t = kb - 4 * word;                   // bytes of this word that come from `a`
+    const uint32_t m = t <= 0 ? 0u : t >= 4 ? 0xFFFFFFFFu : (1u << (8 * t)) - 1u;
+    return (a & m) | (b & ~m);
+}
+template <uint32_t CS>
+__device__ __forceinline__ Chunk32 splice_chunk(const Chunk32 &a, const Chunk32 &b, uint32_t kb)
+{
+    Chunk32 o;
+    const int32_t k = int32_t(kb);
+    o.lo.x = splice_word(a.lo.x, b.lo.x, k, 0);
+    o.lo.y = splice_word(a.lo.y, b.lo.y, k, 1);
+    o.lo.z = splice_word(a.lo.z, b.lo.z, k, 2);
+    o.lo.w = splice_word(a.lo.w, b.lo.w, k, 3);
+    if (CS == 32) {
+        o.hi.x = splice_word(a.hi.x, b.hi.x, k, 4);
+        o.hi.y = splice_word(a.hi.y, b.hi.y, k, 5);
+        o.hi.z = splice_word(a.hi.z, b.hi.z, k, 6);
+        o.hi.w = splice_word(a.hi.w, b.hi.w, k, 7);
+    }
+    return o;
+}
+
+// Spliced path: rows that are not a whole number of chunks (a dim-1 share whose row segment is,
+// say, 2050 bytes).  The output is one contiguous stream; a lane owns one 16-byte aligned chunk of
+// it, i.e. CH consecutive units (bytes when copying, elements when converting).  Most chunks lie
+// inside one row and are read like a byte-aligned vector chunk.  A chunk that straddles a row end
+// takes its first k units from the end of row r and the rest from the start of row r+1: the second
+// read starts k units *before* row r+1 (inside row r's stride, since a row has at least CH units),
+// so that both reads hold their units at the chunk's own positions and a byte mask splices them.
+template <uint32_t CONV>
+__global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const DevDesc *__restrict__ descs,
+                                                                        const uint32_t *__restrict__ hints,
+                                                                        const uint8_t *__restrict__ raw)
+{
+    constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
+    constexpr uint32_t CH = CONV == CONV_COPY ? 16 : 8;                 // units per chunk
+    constexpr uint32_t US = CS / CH;                                    // source bytes per unit
+    const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
+    const PieceRegs d = find_piece(descs, hints, b);
+    const uint32_t t = b - d.tile0();
+    const uint32_t c0 = t * VEC_TILE_UNITS;
+    const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units()) - c0 : VEC_TILE_UNITS;
+    if (threadIdx.x >= n) return;
+    const uint32_t c = c0 + threadIdx.x;
+    const uint32_t u0 = c * CH;                                         // the piece has fewer than 2^31 units
+    const uint32_t upr = d.units_per_row();
+    const uint32_t r = fast_div(u0, d.div_m(), d.div_s());
+    const uint32_t col = u0 - r * upr;
+    const uint8_t *row = raw + d.src_off() + uint64_t(r) * d.src_stride();
+    Chunk32 v;
+    if (CS == 16) v.lo = load16<true>(row + uint64_t(col) * US); else v = load32<true>(row + uint64_t(col) * US);
+    const uint32_t k = upr - col;                                       // units left in row r
+    if (k < CH) {
+        const uint8_t *next = row + d.src_stride() - k * US;
+        Chunk32 w;
+        if (CS == 16) w.lo = load16<true>(next); else w = load32<true>(next);
+        v = splice_chunk<CS>(v, w, k * US);
+    }
+    const Chunk32 o = convert_chunk<CONV>(v);
+    uint8_t *out = reinterpret_cast<uint8_t *>(d.dst()) + uint64_t(c) * CD;
+    gstore16(out, o.lo);
+    if (CD == 32) gstore16(out + 16, o.hi);
+}
+
 // Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
 // byte when nothing is converted) per thread and step; sources are read bytewise.
 template <uint32_t CONV>
@@ -430,6 +497,8 @@ int launch_conv(uint32_t variant, const DevDesc *descs, const uint32_t *hints, u
         hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
     else if (variant == 1)
         hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
+    else if (variant == 3)
+        hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
     else
         hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw);
     const hipError_t e = hipGetLastError();
@@ -445,7 +514,8 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
     if (n_tiles == 0) return FST_OK;
     uint32_t conv, variant;
     if (cls < CONV_COUNT * 2) { conv = cls / 2; variant = cls % 2; }
-    else { conv = cls - CONV_COUNT * 2; variant = 2; }
+    else if (cls < CONV_COUNT * 3) { conv = cls - CONV_COUNT * 2; variant = 2; }
+    else { conv = cls - CONV_COUNT * 3; variant = 3; }
     const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (conv) {

@@ -16,7 +16,7 @@ namespace {
 
 uint32_t tiles_of(const Piece &pc)
 {
-    const uint64_t per = pc.path == PATH_VEC ? VEC_TILE_UNITS : ELEM_TILE_UNITS;
+    const uint64_t per = tile_units(pc.path);
     return uint32_t((pc.n_units + per - 1) / per);
 }
 
@@ -85,7 +85,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         d.units_per_row = pc->units_per_row;
         d.tile0 = r.tiles;
         d.n_tiles = tiles_of(*pc);
-        if (pc->path == PATH_VEC && pc->units_per_row) division_magic(pc->units_per_row, d.div_m, d.div_s);
+        if (pc->path != PATH_ELEM && pc->units_per_row) division_magic(pc->units_per_row, d.div_m, d.div_s);
         if (uint64_t(r.tiles) + d.n_tiles > 0x7FFFFFFFull) return fail(FST_E_RANGE, "too many tiles in one launch");
         r.tiles += d.n_tiles;
         r.count += 1;

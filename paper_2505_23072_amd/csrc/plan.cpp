@@ -89,10 +89,10 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
         const uint64_t per_unit_s = path == PATH_VEC ? chunk * unit_s : unit_s;
         pc.src_span = (nrows - 1) * pc.src_stride + upr * per_unit_s;
         pc.dword_aligned = ((p->raw_base[o.info.file] + soff) % 4 == 0) && (nrows == 1 || o.src_stride % 4 == 0);
-        const uint64_t elems = path == PATH_VEC ? n_units * chunk : n_units;
+        const uint64_t elems = path == PATH_ELEM ? n_units : n_units * chunk;
         pc.read_bytes = elems * unit_s;
         pc.write_bytes = elems * unit_d;
-        const uint64_t tiles = ceil_div(n_units, path == PATH_VEC ? VEC_TILE_UNITS : ELEM_TILE_UNITS);
+        const uint64_t tiles = ceil_div(n_units, tile_units(path));
         if (tiles > (1u << 30)) return fail(FST_E_RANGE, "output %u needs too many tiles", oi);
         g.pieces.push_back(pc);
         g.read_bytes += pc.read_bytes;
@@ -125,6 +125,27 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
             const uint64_t nr = std::min(rows - r, rows_per);
             if (int rc = push(PATH_VEC, src0 + r * o.src_stride, dst0 + r * upr * chunk * unit_d, nr * upr, upr, nr))
                 return rc;
+        }
+    } else if (dst0 % 16 == 0 && row_units >= chunk && row_units < SPLICE_PIECE_MAX_UNITS) {
+        // ragged rows of at least one chunk: chunks are cut from the output stream, which keeps the
+        // stores 16-byte aligned; a chunk that straddles a row end is spliced from two rows.  Unit
+        // indices inside a piece stay below 2^31; pieces are cut after a multiple of 16 rows, which
+        // keeps every piece's first output byte 16-byte aligned.
+        uint64_t rows_per = SPLICE_PIECE_MAX_UNITS / row_units;       // rows whose units fit the index range
+        if (rows > rows_per) rows_per = rows_per / 16 * 16;
+        if (rows_per == 0) {
+            if (int rc = push(PATH_ELEM, src0, dst0, rows * row_units, row_units, rows)) return rc;
+            return FST_OK;
+        }
+        for (uint64_t r = 0; r < rows; r += rows_per) {
+            const uint64_t nr = std::min(rows - r, rows_per);
+            const uint64_t units = nr * row_units, full = units / chunk, tail = units % chunk;
+            const uint64_t s0 = src0 + r * o.src_stride, d0 = dst0 + r * row_units * unit_d;
+            if (int rc = push(PATH_SPLICE, s0, d0, full, row_units, nr)) return rc;
+            if (tail)       // the last units of the last row
+                if (int rc = push(PATH_ELEM, s0 + (nr - 1) * o.src_stride + (row_units - tail) * unit_s,
+                                  d0 + full * chunk * unit_d, tail, tail, 1))
+                    return rc;
         }
     } else {
         if (int rc = push(PATH_ELEM, src0, dst0, rows * row_units, row_units, rows)) return rc;
@@ -281,7 +302,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap)
         // a launch of k pieces with t_i tiles has ceil(sum t_i / HINT_SPAN) <= sum (t_i / HINT_SPAN + 1) hints
         g.hint_bound = 0;
         for (const Piece &pc : g.pieces)
-            g.hint_bound += ceil_div(pc.n_units, pc.path == PATH_VEC ? VEC_TILE_UNITS : ELEM_TILE_UNITS) / HINT_SPAN + 1;
+            g.hint_bound += ceil_div(pc.n_units, tile_units(pc.path)) / HINT_SPAN + 1;
         p->read_bytes += g.read_bytes;
         p->write_bytes += g.write_bytes;
     }

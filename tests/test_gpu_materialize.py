@@ -116,6 +116,39 @@ def test_blocked_and_ragged_rows():
         _check(got, want, [name], [req], f"ragged world {world}")
 
 
+@pytest.mark.parametrize("residue", [0, 1, 2, 7, 12])
+def test_ragged_rows_of_at_least_one_chunk(residue):
+    """Shares whose row segments are not a multiple of 16 bytes (274, 44, 25, 18, 420, 550 and 740 bytes):
+    chunks of the output stream that straddle a row end are spliced from two rows.  Several tiles, tails
+    of one element, every conversion, first and last rank."""
+    rng = np.random.default_rng(300 + residue)
+    spec = [("a", "BF16", (300, 1096), 8), ("b", "F32", (200, 44), 4), ("c", "I8", (300, 100), 4),
+            ("d", "F16", (129, 72), 8), ("e", "BF16", (6, 50, 21), 5), ("f", "BF16", (4099, 1100), 4),
+            ("g", "F32", (1031, 72), 8)]
+    ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
+    ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
+    ts.append(("qkv", "BF16", (120, 37), random_bits(rng, "BF16", (120, 37)).tobytes()))
+    blob = writer.write_file(None, ts, None, residue)
+    for world in (4, 5, 8):
+        names, reqs = [], []
+        for n, dt, shape, w in spec:
+            if w != world:
+                continue
+            for dst in [None] + ([d for d in FLOATS if d != dt] if dt in FLOATS else []):
+                names.append(n)
+                reqs.append((dst, 1, 1))
+        if world == 4:
+            names += ["qkv", "qkv"]
+            reqs += [(None, 0, 3), ("F32", 0, 3)]
+        for rank in (0, world - 1):
+            print(f"residue {residue} world {world} rank {rank}: {len(names)} requests", flush=True)
+            want = oracle_outputs([blob], names, reqs, rank, world)
+            got, _ = materialize_resident([blob], names, reqs, rank, world)
+            _check(got, want, names, reqs, f"world {world} rank {rank}")
+            got, _ = materialize_slots([blob], names, reqs, rank, world, 1 << 20)
+            _check(got, want, names, reqs, f"slots world {world} rank {rank}")
+
+
 @pytest.mark.parametrize("src,dst", [("F16", "BF16"), ("BF16", "F16"), ("F16", "F32"), ("BF16", "F32")])
 def test_exhaustive_16bit_conversions_on_device(src, dst):
     """All 65536 source patterns, NaN payloads and subnormals included, at an odd source offset too."""
