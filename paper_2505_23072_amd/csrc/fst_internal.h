@@ -130,7 +130,8 @@ inline uint32_t tile_units(uint32_t path) { return path == PATH_ELEM ? ELEM_TILE
 constexpr uint32_t XCD_COUNT = 8;
 constexpr uint32_t XCD_RUN = 64;
 // A workgroup finds its piece through a hint table with one entry per HINT_SPAN tiles (the piece
-// that holds the span's first tile) and then steps forward; for large tensors that is no step.
+// that holds the span's first tile) plus a closing entry per launch (its last piece): the owner of
+// a tile lies between its span's entry and the next one; for large tensors the two coincide.
 constexpr uint32_t HINT_SPAN = 64;
 // Vector pieces are cut so that chunk indices inside a piece fit 32 bits.
 constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;
@@ -148,7 +149,8 @@ struct LaunchRange { uint32_t cls, first, count, tiles, hint_first; };
 // Host copy of a device table: pieces, hints, and the launches over them.
 struct TableImage {
     std::vector<DevDesc> descs;
-    std::vector<uint32_t> hints;      // per launch: for tile HINT_SPAN*k, the piece (from the launch's first) holding it
+    std::vector<uint32_t> hints;      // per launch: for tile HINT_SPAN*k, the piece (from the launch's first) holding it,
+                                      //   then the launch's last piece
     std::vector<LaunchRange> ranges;
     std::vector<uint8_t> blob;        // what is copied to the device: descs, then hints at table_hint_offset
     // set by fst_prepare: where the blob was uploaded and the source length it was checked against

@@ -320,16 +320,20 @@ static_assert(offsetof(DevDesc, src_off) == 0 && offsetof(DevDesc, src_stride) =
               offsetof(DevDesc, tile0) == 36 && offsetof(DevDesc, n_tiles) == 40 && offsetof(DevDesc, div_m) == 44 &&
               offsetof(DevDesc, div_s) == 48, "PieceRegs reads DevDesc by dword position");
 
-// The piece that owns tile `b`: the hint names the piece that holds the first tile of b's span of
-// HINT_SPAN tiles; the owner is that piece or one of the next few (none for a large tensor).
-// Every tile index below the launch's tile count belongs to a piece, so the walk ends.
+// The piece that owns tile `b`.  hints[k] names the piece that holds tile k*HINT_SPAN (the last
+// piece for the entry past the end), so the owner lies between hints[b/HINT_SPAN] and the next
+// entry: for a large tensor the two are equal and nothing is searched; a span full of small
+// tensors costs a binary search over first-tile fields, at most log2(HINT_SPAN) steps.
 __device__ __forceinline__ PieceRegs find_piece(const DevDesc *__restrict__ descs,
                                                 const uint32_t *__restrict__ hints, uint32_t b)
 {
-    const u32x16 *d = reinterpret_cast<const u32x16 *>(descs + hints[b / HINT_SPAN]);
+    uint32_t lo = hints[b / HINT_SPAN], hi = hints[b / HINT_SPAN + 1];
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (descs[mid].tile0 <= b) lo = mid; else hi = mid - 1;
+    }
     PieceRegs p;
-    p.w = *d;
-    while (b - p.tile0() >= p.n_tiles()) p.w = *++d;
+    p.w = *reinterpret_cast<const u32x16 *>(descs + lo);
     return p;
 }
 

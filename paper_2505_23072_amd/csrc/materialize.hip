@@ -92,7 +92,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         descs.push_back(d);
     }
     // hints: for every HINT_SPAN-th tile of a launch, the piece (counted from the launch's first)
-    // that holds it
+    // that holds it, and one more entry naming the launch's last piece
     for (LaunchRange &r : ranges) {
         r.hint_first = uint32_t(image.hints.size());
         uint32_t at = 0;
@@ -100,6 +100,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
             while (t - descs[r.first + at].tile0 >= descs[r.first + at].n_tiles) ++at;
             image.hints.push_back(at);
         }
+        image.hints.push_back(r.count - 1);
     }
     // one blob for the upload: pieces, then hints on a 256-byte boundary
     image.blob.assign(table_bytes(descs.size(), image.hints.size()), 0);
