@@ -273,7 +273,9 @@ int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *
  * fst_materialize does, and enqueues the upload into dev_workspace on `stream`.  The workspace
  * then belongs to that group until it is prepared again or the groups are re-cut.
  *
- * fst_launch enqueues only the kernels of a prepared group on `stream`: no copy, no allocation.
+ * fst_launch enqueues only the kernels of a prepared group on `stream`: no copy, no allocation,
+ * no memset, so the call may be recorded into a HIP graph and replayed whenever new raw bytes have
+ * landed in the same buffer.
  * The stream must be the one given to fst_prepare or be ordered after it.  src_dev may differ
  * from call to call (FST_RAW_ALIGN-aligned, device) as long as it holds the same layout and
  * src_len is at least the length the group was prepared with (FST_E_RANGE otherwise); a group

@@ -290,6 +290,39 @@ def test_prepare_once_launch_on_two_source_buffers():
     _check(fetch(bufs, plan), oracle_outputs([blobs[1]], names, reqs, rank, world), names, reqs, "per group")
 
 
+def test_launch_half_replays_from_a_hip_graph():
+    """fst_launch enqueues kernels only, so it can be recorded into a HIP graph once and replayed for every
+    new set of raw bytes that lands in the same buffer (a checkpoint reloaded into place).  Eager work and
+    synchronisations sit between the replays, and every replay is checked against the oracle."""
+    rng = np.random.default_rng(12)
+    shapes = [("w", "BF16", (520, 264)), ("h", "F16", (264, 520)), ("r", "BF16", (300, 1096)), ("v", "F32", (1031,))]
+    names, reqs = ["w", "h", "h", "r", "v"], [(None, 0, 1), ("F32", 0, 2), ("BF16", 1, 1), ("F32", 1, 1), ("BF16", -1, 1)]
+    world, rank = 4, 1
+    blobs = [writer.write_file(None, [(n, d, s, random_bits(rng, d, s).tobytes()) for n, d, s in shapes], None, 3)
+             for _ in range(3)]
+    plan = B.Plan(headers_of(blobs[:1]), [0], names, reqs, rank, world)
+    raw, _, raw_len = upload_resident(blobs[:1])
+    bufs, ptrs = device.alloc_outputs(plan)
+    ws = device.device_bytes(plan.workspace_bytes())
+    s = torch.cuda.Stream()
+    B.fst_prepare(plan, B.FST_ALL_GROUPS, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, ws.data_ptr(), ws.numel(), s.cuda_stream)
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        B.fst_launch(plan, B.FST_ALL_GROUPS, raw.data_ptr(), raw_len, torch.cuda.current_stream().cuda_stream)
+    from util_gpu import fetch
+    for k in (1, 2, 0, 1):
+        host = np.zeros(raw_len, np.uint8)
+        host[:len(blobs[k])] = np.frombuffer(blobs[k], np.uint8)
+        raw.copy_(torch.from_numpy(host))                   # eager work between the replays
+        for b in bufs:
+            b.fill_(0x77)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        _check(fetch(bufs, plan), oracle_outputs([blobs[k]], names, reqs, rank, world), names, reqs, f"replay of file {k}")
+
+
 def test_operand_checks_reject_before_any_launch():
     rng = np.random.default_rng(4)
     blob, ts = make_file(rng, n_tensors=4, big=True)
