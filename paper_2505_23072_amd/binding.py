@@ -13,7 +13,8 @@ from ctypes import (POINTER, Structure, byref, c_char_p, c_double, c_int, c_int3
 from typing import Dict, List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfst.so")
+# FST_LIBRARY names another build of the same ABI (the tests use it for a sanitizer build of the host parts)
+LIB_PATH = os.environ.get("FST_LIBRARY") or os.path.join(_HERE, "libfst.so")
 
 FST_MAX_DIMS = 8
 FST_OUTPUT_ALIGN = 256
