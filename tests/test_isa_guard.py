@@ -53,6 +53,14 @@ def test_no_scc_consumer_without_producer(tmp_path):
     assert "flat_load" not in text and "flat_store" not in text, "generic-address accesses crept back in"
     assert "scratch_" not in text, "register spills"
     assert scc_findings(text) == []
+    # the conversion instructions depend on the kernels' floating-point mode: round to nearest even,
+    # denormals kept for every width (a flush-to-zero or fast-math build flag would change these)
+    n_kernels = len(re.findall(r"^\s*\.amdhsa_kernel ", text, flags=re.M))
+    assert n_kernels >= 28
+    for directive, value in ((".amdhsa_float_round_mode_32", 0), (".amdhsa_float_round_mode_16_64", 0),
+                             (".amdhsa_float_denorm_mode_32", 3), (".amdhsa_float_denorm_mode_16_64", 3)):
+        found = re.findall(rf"^\s*{re.escape(directive)}\s+(\d+)", text, flags=re.M)
+        assert len(found) == n_kernels and all(int(v) == value for v in found), (directive, sorted(set(found)))
 
 
 def test_checker_catches_the_known_bad_shape():
