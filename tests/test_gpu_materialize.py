@@ -116,6 +116,24 @@ def test_blocked_and_ragged_rows():
         _check(got, want, [name], [req], f"ragged world {world}")
 
 
+def test_hand_derived_partitions_and_conversions():
+    """The kernels against results worked out by hand (tests/golden/handmade_partition.txt): one plan
+    per request, and all requests of a (rank, world) pair in one plan."""
+    from util_golden import load_fixture
+    g = load_fixture("handmade_partition.txt")
+    blob = g["file"]
+    for nm, dst, dim, blocks, rank, world, shape, want in g["parts"]:
+        got, plan = materialize_resident([blob], [nm], [(dst, dim, blocks)], rank, world)
+        assert plan.output(0)["shape"] == shape and got == [want], (nm, dst, dim, blocks, rank, world)
+    names = [p[0] for p in g["parts"]]
+    reqs = [(p[1], p[2], p[3], p[4]) for p in g["parts"]]
+    worlds = sorted({p[5] for p in g["parts"]})
+    for world in worlds:
+        sel = [i for i, p in enumerate(g["parts"]) if p[5] == world]
+        got, _ = materialize_resident([blob], [names[i] for i in sel], [reqs[i] for i in sel], 0, world)
+        assert got == [g["parts"][i][7] for i in sel], f"world {world}"
+
+
 @pytest.mark.parametrize("residue", [0, 1, 2, 7, 12])
 def test_ragged_rows_of_at_least_one_chunk(residue):
     """Shares whose row segments are not a multiple of 16 bytes (274, 44, 25, 18, 420, 550 and 740 bytes):

@@ -17,7 +17,7 @@ CLASS = {"TRUNCATED": "FST_E_TRUNCATED", "HEADER_SIZE": "FST_E_HEADER_SIZE", "JS
          "OFFSETS": "FST_E_OFFSETS", "DUPLICATE": "FST_E_DUP_NAME", "RANGE": "FST_E_RANGE"}
 
 
-@pytest.mark.parametrize("fx", ["handmade_two.txt", "handmade_odd.txt"])
+@pytest.mark.parametrize("fx", ["handmade_two.txt", "handmade_odd.txt", "handmade_partition.txt"])
 def test_handmade_fixture(fx):
     g = load_fixture(fx)
     h = B.Header(g["file"], len(g["file"]))

@@ -175,6 +175,19 @@ def test_sparse_staging_leaves_out_what_no_request_reads():
     assert [len(plan.group(g)["extents"]) for g in range(ng)] == [1] * ng
 
 
+def test_hand_derived_partitions_and_conversions():
+    """The planner's descriptors, run on the CPU, against results worked out by hand
+    (tests/golden/handmade_partition.txt)."""
+    from util_golden import load_fixture
+    g = load_fixture("handmade_partition.txt")
+    blob = g["file"]
+    h = _headers([blob])
+    for nm, dst, dim, blocks, rank, world, shape, want in g["parts"]:
+        plan = B.Plan(h, [0], [nm], [(dst, dim, blocks)], rank, world)
+        assert plan.output(0)["shape"] == shape and plan.output(0)["nbytes"] == len(want)
+        assert _interpret(plan, [blob]) == [want], (nm, dst, dim, blocks, rank, world)
+
+
 def test_plan_errors():
     from synth import writer
     a = np.zeros(24, np.uint16).tobytes()

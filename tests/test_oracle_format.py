@@ -21,7 +21,7 @@ def _name_of(fixture_name: str) -> str:
         return fixture_name
 
 
-@pytest.mark.parametrize("fx", ["handmade_two.txt", "handmade_odd.txt"])
+@pytest.mark.parametrize("fx", ["handmade_two.txt", "handmade_odd.txt", "handmade_partition.txt"])
 def test_handmade_fixture(fx, tmp_path):
     g = load_fixture(fx)
     blob = g["file"]

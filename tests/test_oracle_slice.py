@@ -128,3 +128,17 @@ def test_threaded_fan_out_matches_single_calls():
     orc.materialize_jobs(jobs, 4)
     for j, r in zip(jobs, refs):
         assert j["out"].tobytes() == r.tobytes()
+
+
+def test_hand_derived_partitions_and_conversions():
+    """Partitions and conversions worked out by hand (tests/golden/handmade_partition.txt)."""
+    from util_golden import load_fixture
+    g = load_fixture("handmade_partition.txt")
+    blob = g["file"]
+    tab = orc.parse(blob, len(blob))
+    assert len(g["parts"]) >= 9
+    for nm, dst, dim, blocks, rank, world, shape, want in g["parts"]:
+        t = tab.find(nm)
+        stored = np.frombuffer(blob, np.uint8, t.end - t.begin, tab.body_off + t.begin)
+        out, got_shape = orc.materialize(stored, t.dtype, t.shape, dst, dim, blocks, rank, world)
+        assert got_shape == shape and out.tobytes() == want, (nm, dst, dim, blocks, rank, world)
