@@ -1,7 +1,7 @@
 // Host side of fst_materialize: checks the operands against what the kernels assume, builds the
 // device table of pieces for one group (or all), copies it into the caller's workspace and
 // launches one kernel per launch class (paper Section III-B: preprocessing offloaded to the GPU).
-#include <hip/hip_runtime.h>
+#include <hip/hip_runtime_api.h>
 
 #include <algorithm>
 #include <cstring>

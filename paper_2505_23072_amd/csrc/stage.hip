@@ -8,7 +8,7 @@
 // the group's kernels.  Kernels of group g therefore run while the bytes of group g+1 are still
 // crossing PCIe.  For checkpoints larger than device memory the raw buffer is itself a ring of
 // device slots; a slot is overwritten only after the kernels of its previous group are done.
-#include <hip/hip_runtime.h>
+#include <hip/hip_runtime_api.h>
 
 #include <algorithm>
 #include <atomic>
