@@ -42,18 +42,23 @@ def log(*a):
 
 
 def kernel_sources_digest() -> str:
+    """SHA-256 of the kernel sources with comments and white space taken out: what decides the code."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for f in KERNEL_SOURCES:
-        with open(f, "rb") as fh:
-            h.update(fh.read())
+        with open(f, encoding="utf-8") as fh:
+            text = fh.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()
 
 
 def recorded_traffic(kernel: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size), or None when
-    there is no summary for this workload or the kernel sources changed after it was taken."""
+    there is no summary for this workload or the kernel sources (comments aside) changed after it was taken."""
     try:
         text = open(PMC_SUMMARY).read()
     except OSError:

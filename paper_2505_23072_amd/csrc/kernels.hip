@@ -4,10 +4,10 @@
 //
 // Work is a table of pieces (DevDesc).  One workgroup of 1024 threads = 16 wavefronts takes one
 // tile of a piece; the piece is found through a hint table (one entry per HINT_SPAN tiles) with
-// scalar loads, since it only depends on the workgroup index.  In the vector path a lane moves one
-// chunk: 16 source bytes when nothing is converted, 8 elements otherwise, always written with
-// full 16-byte stores to a 16-byte aligned destination.  Latency is covered by occupancy (two
-// workgroups = 32 wavefronts per CU), not by several loads per lane.
+// scalar loads, since it only depends on the workgroup index.  In the vector and spliced paths a
+// lane moves one chunk: 16 source bytes when nothing is converted, 8 elements otherwise, always
+// written with full 16-byte stores to a 16-byte aligned destination.  Latency is covered by
+// occupancy (two workgroups = 32 wavefronts per CU), not by several loads per lane.
 //
 // The source may start at any byte.  Sources that are a multiple of 4 are read with 4-byte
 // aligned 16-byte loads.  Others read the enclosing aligned dwords (one more than the chunk
@@ -457,8 +457,9 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const De
     if (CD == 32) gstore16(out + 16, o.hi);
 }
 
-// Element path: ragged tails and rows that are not a whole number of chunks.  One element (one
-// byte when nothing is converted) per thread and step; sources are read bytewise.
+// Element path: tails shorter than a chunk, rows shorter than a chunk, and pieces whose first
+// output byte is not 16-byte aligned.  One element (one byte when nothing is converted) per thread
+// and step; sources are read bytewise; indices are 64-bit.
 template <uint32_t CONV>
 __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
                                                                        const uint32_t *__restrict__ hints,
