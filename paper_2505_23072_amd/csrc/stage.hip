@@ -252,7 +252,7 @@ using namespace fst;
 
 extern "C" {
 
-int fst_stager_create(const fst_stager_config *cfg, fst_stager **out)
+static int stager_create_impl(const fst_stager_config *cfg, fst_stager **out)
 {
     if (!out) return fail(FST_E_ARG, "fst_stager_create: out is NULL");
     *out = nullptr;
@@ -273,13 +273,30 @@ int fst_stager_create(const fst_stager_config *cfg, fst_stager **out)
     if (e != hipSuccess) { s->pinned = nullptr; return cleanup("hipHostMalloc", e); }
     if ((e = hipStreamCreateWithFlags(&s->copy, hipStreamNonBlocking)) != hipSuccess) return cleanup("hipStreamCreate", e);
     if ((e = hipStreamCreateWithFlags(&s->compute, hipStreamNonBlocking)) != hipSuccess) return cleanup("hipStreamCreate", e);
+    try {
+        s->slot_done.reserve(s->n_slots);
+    } catch (...) {
+        fst_stager_destroy(s);
+        throw;
+    }
     for (uint32_t i = 0; i < s->n_slots; ++i) {
         hipEvent_t ev;
         if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return cleanup("hipEventCreate", e);
-        s->slot_done.push_back(ev);
+        s->slot_done.push_back(ev);         // reserved above: cannot throw
     }
     *out = s;
     return FST_OK;
+}
+
+int fst_stager_create(const fst_stager_config *cfg, fst_stager **out)
+{
+    try {
+        return stager_create_impl(cfg, out);
+    } catch (const std::bad_alloc &) {
+        return fail(FST_E_NOMEM, "out of memory");
+    } catch (...) {
+        return fail(FST_E_ARG, "unexpected internal error");
+    }
 }
 
 void fst_stager_destroy(fst_stager *s)
