@@ -187,9 +187,15 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     sh.issued.assign(nb, 0);
     std::vector<std::thread> threads;
     const uint32_t nt = uint32_t(std::min<size_t>(s->n_threads, std::max<size_t>(nb, 1)));
-    for (uint32_t t = 0; t < nt; ++t) threads.emplace_back(reader, s, &blocks, &sh, read, ctx, skip_read);
-
     int status = FST_OK;
+    try {
+        threads.reserve(nt);
+        for (uint32_t t = 0; t < nt; ++t) threads.emplace_back(reader, s, &blocks, &sh, read, ctx, skip_read);
+    } catch (...) {
+        // a thread could not be started: stop the ones that run, report, copy nothing
+        status = fail(FST_E_NOMEM, "could not start %u reader threads", nt);
+    }
+
     uint64_t staged = 0;
     hipEvent_t ready = s->events[0];
     for (size_t i = 0; i < nb && status == FST_OK; ++i) {
