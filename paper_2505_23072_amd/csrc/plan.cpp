@@ -101,21 +101,24 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
     };
     (void)base_abs;
 
-    if (rows == 1 && dst0 % 16) {
-        // a cut inside an output with ragged rows: the vector path needs 16-byte aligned stores
-        if (int rc = push(PATH_ELEM, src0, dst0, row_units, row_units, 1)) return rc;
-    } else if (rows == 1) {
-        const uint64_t full = row_units / chunk, tail = row_units % chunk;
-        // one long row, in pieces whose chunk indices fit 32 bits
+    if (rows == 1) {
+        // one long row.  When it does not start on a 16-byte boundary of the output (a cut inside an
+        // output with ragged rows), the units up to the next boundary go through the element path.
+        const uint64_t head = std::min<uint64_t>(row_units, (16 - dst0 % 16) % 16 / unit_d);
+        if (head)
+            if (int rc = push(PATH_ELEM, src0, dst0, head, head, 1)) return rc;
+        const uint64_t s1 = src0 + head * unit_s, d1 = dst0 + head * unit_d;
+        const uint64_t full = (row_units - head) / chunk, tail = (row_units - head) % chunk;
+        // the body, in pieces whose chunk indices fit 32 bits
         for (uint64_t c = 0; c < full; c += VEC_PIECE_MAX_UNITS) {
             const uint64_t n = std::min(full - c, VEC_PIECE_MAX_UNITS);
-            if (int rc = push(PATH_VEC, src0 + c * chunk * unit_s, dst0 + c * chunk * unit_d, n, 1, 1)) return rc;
+            if (int rc = push(PATH_VEC, s1 + c * chunk * unit_s, d1 + c * chunk * unit_d, n, 1, 1)) return rc;
             Piece &pc = g.pieces.back();
             pc.units_per_row = 0;       // 0 = a single row of any length
             pc.src_span = n * chunk * unit_s;
         }
         if (tail)
-            if (int rc = push(PATH_ELEM, src0 + full * chunk * unit_s, dst0 + full * chunk * unit_d, tail, tail, 1))
+            if (int rc = push(PATH_ELEM, s1 + full * chunk * unit_s, d1 + full * chunk * unit_d, tail, tail, 1))
                 return rc;
     } else if (row_units % chunk == 0) {
         const uint64_t upr = row_units / chunk;
