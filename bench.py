@@ -90,6 +90,9 @@ def main() -> int:
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--all-ranks", action="store_true",
+                    help="tensor-parallel workloads: every rank's share of every split tensor from one plan and one "
+                         "launch set (replicated tensors once)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
     ap.add_argument("--min-gap", type=int, default=None,
                     help="end-to-end leg: do not stage unread file ranges longer than this many bytes "
@@ -134,8 +137,13 @@ def main() -> int:
         else:
             paths = []
             log(f"{spec.name}: {len(sizes)} files, {sum(sizes) / 1e9:.2f} GB from the procedural source (not stored)")
-        names = [t.name for f in spec.files for t in f.tensors]
-        reqs = [(t.dst_dtype, t.shard_dim, t.blocks) for f in spec.files for t in f.tensors]
+        names, reqs = [], []
+        for f in spec.files:
+            for t in f.tensors:
+                ranks = range(spec.world) if args.all_ranks and t.shard_dim >= 0 else [-1]
+                for r in ranks:
+                    names.append(t.name)
+                    reqs.append((t.dst_dtype, t.shard_dim, t.blocks, r) if r >= 0 else (t.dst_dtype, t.shard_dim, t.blocks))
         bases, raw_len = device.file_bases(sizes)
 
         def parse_and_plan(group_bytes, min_gap=None):
@@ -279,7 +287,7 @@ def main() -> int:
             nbytes = [g["read_bytes"] + g["write_bytes"] for g in groups]
             dom = int(np.argmax(nbytes))
             align = len(model.headers[groups[dom]["file"]]) % 16
-            if all(r == (None, -1, 1) for r in reqs):
+            if all(r[:3] == (None, -1, 1) for r in reqs):
                 kernel = "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>"
             else:
                 kernel = "materialize kernels of the largest file (its conversions and partitions)"
@@ -314,7 +322,8 @@ def main() -> int:
             "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "u8" if all(r[0] is None for r in reqs) else "u16", "data": "synthetic",
             "config": {"workload": f"{spec.name}{cut}: {spec.n_tensors} tensors, {len(sizes)} files, {sum(sizes)} bytes, "
-                                   f"N(0,0.02), {describe_requests(spec)}",
+                                   f"N(0,0.02), {describe_requests(spec)}"
+                                   + (f", all {spec.world} ranks' shares in one pass" if args.all_ranks and spec.world > 1 else ""),
                        "bytes_read": rd, "bytes_written": wr,
                        "step": "parse headers + plan + table upload + materialize kernels, raw bytes resident in HBM"},
             "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
