@@ -97,8 +97,8 @@ def main() -> int:
     ap.add_argument("--min-gap", type=int, default=None,
                     help="end-to-end leg: do not stage unread file ranges longer than this many bytes "
                          "(default: stage each group from its first to its last needed byte)")
-    ap.add_argument("--slots", type=int, default=16)
-    ap.add_argument("--slot-bytes", type=int, default=32 << 20)
+    ap.add_argument("--slots", type=int, default=8)
+    ap.add_argument("--slot-bytes", type=int, default=128 << 20)
     ap.add_argument("--threads", type=int, default=12)
     args = ap.parse_args()
     if args.gpus != 1:

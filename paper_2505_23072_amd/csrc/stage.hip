@@ -2,8 +2,10 @@
 // blocks into a small DMA-able bounce buffer in host memory and copies them to the GPU from
 // there; Section IV: up to 16 I/O threads, 160 MB of bounce buffer each).
 //
-// Reader threads fill ring slots; the calling thread is the only one that talks to the GPU: it
-// issues one hipMemcpyAsync per filled slot on the copy stream, in block order, and as soon as
+// Reader threads fill ring slots, several threads per slot (a block is read in parts, so a slot
+// is full after a fraction of the time one thread would need, while the copy out of it stays one
+// large transfer); the calling thread is the only one that talks to the GPU: it issues one
+// hipMemcpyAsync per filled slot on the copy stream, in block order, and as soon as
 // the last block of a group is queued it makes the compute stream wait for that copy and queues
 // the group's kernels.  Kernels of group g therefore run while the bytes of group g+1 are still
 // crossing PCIe.  For checkpoints larger than device memory the raw buffer is itself a ring of
@@ -47,10 +49,17 @@ struct Block {
     bool first, last;        // of its group
 };
 
+// A block is read in parts of part_bytes by whichever reader thread comes next.
+struct Part {
+    uint32_t block;
+    uint64_t off, len;       // inside the block
+};
+
 struct Shared {
     std::mutex mu;
     std::condition_variable cv;
     std::vector<uint8_t> filled, issued;
+    std::vector<uint32_t> parts_left;        // per block, guarded by mu
     bool abort = false;
     int status = FST_OK;
     std::atomic<size_t> next{0};
@@ -72,12 +81,15 @@ int ensure_events(fst_stager *s, size_t n)
     return FST_OK;
 }
 
-void reader(fst_stager *s, const std::vector<Block> *blocks, Shared *sh, fst_read_fn read, void *ctx, bool skip_read)
+void reader(fst_stager *s, const std::vector<Block> *blocks, const std::vector<Part> *parts, Shared *sh,
+            fst_read_fn read, void *ctx, bool skip_read)
 {
-    const size_t n = blocks->size();
+    const size_t n = parts->size();
     for (;;) {
-        const size_t i = sh->next.fetch_add(1);
-        if (i >= n) return;
+        const size_t k = sh->next.fetch_add(1);
+        if (k >= n) return;
+        const Part &pt = (*parts)[k];
+        const size_t i = pt.block;
         const uint32_t slot = uint32_t(i % s->n_slots);
         if (i >= s->n_slots) {
             // the slot's previous block must have been copied out
@@ -98,7 +110,7 @@ void reader(fst_stager *s, const std::vector<Block> *blocks, Shared *sh, fst_rea
         int rc = 0;
         if (!skip_read) {
             const auto t0 = std::chrono::steady_clock::now();
-            rc = read(ctx, int32_t(b.file), b.off, s->pinned + uint64_t(slot) * s->slot_bytes, b.len);
+            rc = read(ctx, int32_t(b.file), b.off + pt.off, s->pinned + uint64_t(slot) * s->slot_bytes + pt.off, pt.len);
             sh->read_ns += uint64_t(std::chrono::duration_cast<std::chrono::nanoseconds>(
                                         std::chrono::steady_clock::now() - t0).count());
         }
@@ -106,10 +118,12 @@ void reader(fst_stager *s, const std::vector<Block> *blocks, Shared *sh, fst_rea
         if (rc) {
             sh->abort = true;
             sh->status = fail(FST_E_IO, "read of file %u at %llu (+%llu) failed", b.file,
-                              (unsigned long long)b.off, (unsigned long long)b.len);
+                              (unsigned long long)(b.off + pt.off), (unsigned long long)pt.len);
         }
-        sh->filled[i] = 1;
-        sh->cv.notify_all();
+        if (--sh->parts_left[i] == 0 || rc) {
+            sh->filled[i] = 1;
+            sh->cv.notify_all();
+        }
         if (rc) return;
     }
 }
@@ -182,15 +196,24 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     const size_t nb = blocks.size();
     if (int rc = ensure_events(s, streamed ? n_dev_slots + 1 : 1)) return rc;
 
+    // parts of a sixteenth of a slot (4 KiB .. 8 MiB): the threads fill one slot together
+    const uint64_t part_bytes = std::min<uint64_t>(std::max<uint64_t>((s->slot_bytes / 16 + 4095) / 4096 * 4096, 4096), 8ull << 20);
+    std::vector<Part> parts;
     Shared sh;
     sh.filled.assign(nb, 0);
     sh.issued.assign(nb, 0);
+    sh.parts_left.assign(nb, 0);
+    for (size_t i = 0; i < nb; ++i)
+        for (uint64_t o = 0; o < blocks[i].len; o += part_bytes) {
+            parts.push_back(Part{uint32_t(i), o, std::min<uint64_t>(part_bytes, blocks[i].len - o)});
+            ++sh.parts_left[i];
+        }
     std::vector<std::thread> threads;
-    const uint32_t nt = uint32_t(std::min<size_t>(s->n_threads, std::max<size_t>(nb, 1)));
+    const uint32_t nt = uint32_t(std::min<size_t>(s->n_threads, std::max<size_t>(parts.size(), 1)));
     int status = FST_OK;
     try {
         threads.reserve(nt);
-        for (uint32_t t = 0; t < nt; ++t) threads.emplace_back(reader, s, &blocks, &sh, read, ctx, skip_read);
+        for (uint32_t t = 0; t < nt; ++t) threads.emplace_back(reader, s, &blocks, &parts, &sh, read, ctx, skip_read);
     } catch (...) {
         // a thread could not be started: stop the ones that run, report, copy nothing
         status = fail(FST_E_NOMEM, "could not start %u reader threads", nt);
