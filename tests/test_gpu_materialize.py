@@ -199,7 +199,9 @@ def test_f32_conversions_on_device(dst):
 @pytest.mark.parametrize("dst", ["BF16", "F16"])
 def test_every_binary32_pattern_on_device(dst):
     """All 2^32 binary32 inputs, in slabs of 2^27, the source one byte off dword alignment in every
-    other slab.  The oracle side runs on a thread pool (its conversion is a plain C loop)."""
+    other slab.  The oracle side runs on a thread pool (its conversion is a plain C loop) and is itself
+    compared with torch's CPU conversion on every input that is not a NaN (numpy's binary16 conversion,
+    a second library, pins it on a sample in the CPU tests; over 2^32 inputs it would take minutes)."""
     from concurrent.futures import ThreadPoolExecutor
 
     from synth import writer as w
@@ -223,6 +225,12 @@ def test_every_binary32_pattern_on_device(dst):
             torch.cuda.synchronize()
             got = bufs[0][:2 * n].cpu().numpy().view(np.uint16)
             want = np.concatenate(list(want))
+            # the oracle itself against torch's CPU conversion on every non-NaN input
+            finite = (x & np.uint32(0x7FFFFFFF)) <= np.uint32(0x7F800000)
+            tdt = torch.float16 if dst == "F16" else torch.bfloat16
+            lib_bits = torch.from_numpy(x.view(np.float32)).to(tdt).view(torch.int16).numpy().view(np.uint16)
+            off = np.nonzero((lib_bits != want) & finite)[0]
+            assert len(off) == 0, f"oracle F32->{dst} differs from the library conversion at input {int(x[off[0]]):#010x}"
             bad = np.nonzero(got != want)[0]
             assert len(bad) == 0, (f"F32->{dst} slab {slab}: {len(bad)} differ, first input {int(x[bad[0]]):#010x} "
                                    f"got {int(got[bad[0]]):#06x} want {int(want[bad[0]]):#06x}")
