@@ -50,7 +50,9 @@ class Fds:
 
 @pytest.mark.parametrize("seed,slots,threads,slot_bytes,group_bytes,gap", [
     (0, 3, 4, 4096, 16384, None), (1, 2, 1, 4096, 4096, None), (2, 8, 8, 65536, 1 << 20, None), (3, 1, 3, 8192, 0, None),
-    (4, 5, 2, 4096, 50000, None), (5, 3, 4, 4096, 16384, 0), (6, 4, 2, 8192, 0, 1000)])
+    (4, 5, 2, 4096, 50000, None), (5, 3, 4, 4096, 16384, 0), (6, 4, 2, 8192, 0, 1000),
+    # slots of many parts: several reader threads fill one slot together
+    (7, 3, 8, 131072, 1 << 20, None), (8, 2, 16, 262144, 0, 500), (9, 1, 12, 65536, 0, None)])
 def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, gap, tmp_path):
     blobs, paths, names, reqs, rank, world = _case(seed, tmp_path)
     print(f"seed {seed} ring {slots}x{slot_bytes} threads {threads} groups {group_bytes}", flush=True)
