@@ -1,5 +1,5 @@
 // Drives the staging ring on the fake runtime: a synthetic file of many small tensors held in
-// memory, tiny ring slots, several reader threads; resident and streamed runs.  Checks that the
+// memory, small ring slots that several reader threads fill together; resident and streamed runs.  Checks that the
 // staged bytes are the file's bytes and that the first byte of every output arrived; the race
 // detector watches the rest.  Exit code 0 = all checks passed.
 #include <cstdio>
@@ -78,7 +78,7 @@ int main()
         CHECK(fst_plan_uniform(hdrs.data(), streamed ? zero.data() : bases.data(), files.size(), cnames.data(), cnames.size(),
                                FST_KEEP, -1, 0, 1, &plan) == FST_OK);
         size_t ng = 0;
-        CHECK(fst_plan_set_groups(plan, 16384, &ng) == FST_OK && ng > 10);
+        CHECK(fst_plan_set_groups(plan, 65536, &ng) == FST_OK && ng > 5);
         const size_t n_out = fst_plan_output_count(plan);
         std::vector<std::vector<uint8_t>> outs(n_out);
         std::vector<void *> ptrs(n_out);
@@ -90,7 +90,7 @@ int main()
         }
         std::vector<uint8_t> ws_store(fst_plan_workspace_bytes(plan) + 256);
         void *ws = reinterpret_cast<void *>((reinterpret_cast<uintptr_t>(ws_store.data()) + 255) / 256 * 256);
-        fst_stager_config cfg{5, 4, 4096};
+        fst_stager_config cfg{3, 6, 16384};      // blocks of up to 16 KiB, read in four parts
         fst_stager *st = nullptr;
         CHECK(fst_stager_create(&cfg, &st) == FST_OK);
         fst_stage_stats stats{};
@@ -106,11 +106,11 @@ int main()
                 CHECK(std::memcmp(raw + bases[f] + 8 + n, files[f].bytes.data() + 8 + n, files[f].bytes.size() - 8 - n) == 0);
             }
         } else {
-            std::vector<std::vector<uint8_t>> slot_store(3, std::vector<uint8_t>(16384 + 512));
+            std::vector<std::vector<uint8_t>> slot_store(3, std::vector<uint8_t>(65536 + 512));
             std::vector<void *> slots;
             for (auto &s : slot_store) slots.push_back(reinterpret_cast<void *>((reinterpret_cast<uintptr_t>(s.data()) + 255) / 256 * 256));
             for (int rep = 0; rep < 3; ++rep)
-                CHECK(fst_stage_streamed(st, plan, read_mem, files.data(), slots.data(), slots.size(), 16384, ptrs.data(), ws,
+                CHECK(fst_stage_streamed(st, plan, read_mem, files.data(), slots.data(), slots.size(), 65536, ptrs.data(), ws,
                                          fst_plan_workspace_bytes(plan), 0, &stats) == FST_OK);
         }
         // the stand-in for a kernel copies the first source byte of every piece to its output
