@@ -560,7 +560,62 @@ uint16_t orc_f32_to_f16(uint32_t x)
     return (uint16_t)(s | q);
 }
 
+/* binary32 (1-8-23, bias 127) -> binary64 (1-11-52, bias 1023): always exact. */
+uint64_t orc_f32_to_f64(uint32_t x)
+{
+    uint64_t s = (uint64_t)(x >> 31) << 63;
+    uint64_t e = (x >> 23) & 0xFFu;
+    uint64_t m = x & 0x7FFFFFu;
+    if (e == 0) {
+        if (m == 0) return s;                                    /* +-0 */
+        /* subnormal: value = m * 2^-149; normalize so that the leading 1 becomes implicit */
+        int k = 22;
+        while (!((m >> k) & 1u)) k--;
+        return s | ((uint64_t)(874 + k) << 52) | ((m << (52 - k)) & 0xFFFFFFFFFFFFFull);
+    }
+    if (e == 255) {
+        if (m == 0) return s | 0x7FF0000000000000ull;            /* infinity */
+        return s | 0x7FF0000000000000ull | (m << 29) | 0x0008000000000000ull;   /* NaN */
+    }
+    return s | ((e + 896u) << 52) | (m << 29);
+}
+
+/* binary64 -> binary32 with RNE. */
+uint32_t orc_f64_to_f32(uint64_t x)
+{
+    uint32_t s = (uint32_t)(x >> 32) & 0x80000000u;
+    uint64_t a = x & 0x7FFFFFFFFFFFFFFFull;
+    uint64_t e = a >> 52;
+    uint64_t m = a & 0xFFFFFFFFFFFFFull;
+    if (a > 0x7FF0000000000000ull) return s | 0x7F800000u | 0x00400000u | (uint32_t)((a >> 29) & 0x3FFFFFu);
+    if (e > 1023u + 127u) return s | 0x7F800000u;                /* 2^128 and above, infinity */
+    if (e >= 897u) {                                             /* result is normal (or rounds up to infinity) */
+        uint32_t r = (uint32_t)((e - 896u) << 23) | (uint32_t)(m >> 29);
+        uint64_t rem = m & 0x1FFFFFFFull, half = 0x10000000ull;
+        if (rem > half || (rem == half && (r & 1u))) r++;        /* a carry moves the exponent up, to infinity at most */
+        return s | r;
+    }
+    if (e < 872u) return s;                                      /* below 2^-151: rounds to zero */
+    /* result is subnormal: q = round(value / 2^-149), value = M * 2^(e-1075) */
+    uint64_t M = m | 0x10000000000000ull;
+    uint64_t sh = 926u - e;                                      /* 30 .. 54 */
+    uint64_t q = M >> sh;
+    uint64_t rem = M & (((uint64_t)1 << sh) - 1u);
+    uint64_t half = (uint64_t)1 << (sh - 1);
+    if (rem > half || (rem == half && (q & 1u))) q++;
+    return s | (uint32_t)q;
+}
+
 static int is_float_dtype(int d) { return d == ORC_F32 || d == ORC_F16 || d == ORC_BF16; }
+
+/* Conversions that exist: among F32, F16, BF16, and between F64 and F32 (a 16-bit type and F64
+ * would need a single rounding from 53 bits, which going through binary32 does not give). */
+static int can_convert(int sd, int dd)
+{
+    if (sd == dd) return 1;
+    if (is_float_dtype(sd) && is_float_dtype(dd)) return 1;
+    return (sd == ORC_F64 && dd == ORC_F32) || (sd == ORC_F32 && dd == ORC_F64);
+}
 
 static uint64_t load_le(const uint8_t *p, uint64_t es)
 {
@@ -579,6 +634,8 @@ static void store_le(uint8_t *p, uint64_t es, uint64_t v)
 static uint64_t convert(uint64_t v, int sd, int dd)
 {
     if (sd == dd) return v;
+    if (sd == ORC_F64) return orc_f64_to_f32(v);
+    if (dd == ORC_F64) return orc_f32_to_f64((uint32_t)v);
     uint32_t f;
     if (sd == ORC_F32) f = (uint32_t)v;
     else if (sd == ORC_F16) f = orc_f16_to_f32((uint16_t)v);
@@ -591,7 +648,7 @@ static uint64_t convert(uint64_t v, int sd, int dd)
 int orc_cast_array(const uint8_t *src, uint64_t n, int sd, int dd, uint8_t *dst)
 {
     if (sd < 0 || sd >= ORC_NDTYPES || dd < 0 || dd >= ORC_NDTYPES) return ORC_DTYPE;
-    if (sd != dd && !(is_float_dtype(sd) && is_float_dtype(dd))) return ORC_CAST;
+    if (!can_convert(sd, dd)) return ORC_CAST;
     uint64_t ss = orc_dtype_size(sd), ds = orc_dtype_size(dd);
     for (uint64_t i = 0; i < n; i++) store_le(dst + i * ds, ds, convert(load_le(src + i * ss, ss), sd, dd));
     return ORC_OK;
@@ -606,7 +663,7 @@ int orc_result_info(int sd, int ndim, const uint64_t *shape, int dd, int shard_d
     if (dd < 0) dd = sd;
     if (dd >= ORC_NDTYPES) return ORC_DTYPE;
     if (ndim < 0 || ndim > ORC_MAX_DIMS) return ORC_RANGE;
-    if (sd != dd && !(is_float_dtype(sd) && is_float_dtype(dd))) return ORC_CAST;
+    if (!can_convert(sd, dd)) return ORC_CAST;
     if (world < 1 || rank < 0 || rank >= world || blocks < 1) return ORC_SHARD;
     if (shard_dim < 0 && blocks != 1) return ORC_SHARD;
     if (shard_dim >= ndim) return ORC_SHARD;                     /* e.g. dim 1 of a vector */

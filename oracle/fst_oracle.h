@@ -34,7 +34,7 @@ enum {
     ORC_DUPLICATE = 8,      /* the same key twice */
     ORC_NOT_FOUND = 9,
     ORC_SHARD = 10,         /* bad dim / rank / world / blocks, or dim not divisible */
-    ORC_CAST = 11,          /* conversion outside {F32, F16, BF16} */
+    ORC_CAST = 11,          /* conversion outside {F32, F16, BF16} and F64 <-> F32 */
     ORC_RANGE = 12,         /* output buffer too small, too many dims */
     ORC_IO = 13,
     ORC_NOMEM = 14
@@ -88,6 +88,8 @@ uint32_t orc_bf16_to_f32(uint16_t x);
 uint32_t orc_f16_to_f32(uint16_t h);
 uint16_t orc_f32_to_bf16(uint32_t x);
 uint16_t orc_f32_to_f16(uint32_t x);
+uint64_t orc_f32_to_f64(uint32_t x);
+uint32_t orc_f64_to_f32(uint64_t x);
 /* n elements of src_dtype at src -> dst_dtype at dst. */
 int orc_cast_array(const uint8_t *src, uint64_t n, int src_dtype, int dst_dtype, uint8_t *dst);
 

@@ -75,7 +75,9 @@ def lib() -> ctypes.CDLL:
         for fn, a, r in [("orc_bf16_to_f32", ctypes.c_uint16, ctypes.c_uint32),
                          ("orc_f16_to_f32", ctypes.c_uint16, ctypes.c_uint32),
                          ("orc_f32_to_bf16", ctypes.c_uint32, ctypes.c_uint16),
-                         ("orc_f32_to_f16", ctypes.c_uint32, ctypes.c_uint16)]:
+                         ("orc_f32_to_f16", ctypes.c_uint32, ctypes.c_uint16),
+                         ("orc_f32_to_f64", ctypes.c_uint32, ctypes.c_uint64),
+                         ("orc_f64_to_f32", ctypes.c_uint64, ctypes.c_uint32)]:
             getattr(L, fn).argtypes = [a]
             getattr(L, fn).restype = r
         L.orc_cast_array.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
@@ -156,8 +158,8 @@ def parse(head: bytes, file_size: int) -> Table:
 def cast_array(src: np.ndarray, src_dtype: str, dst_dtype: str) -> np.ndarray:
     """src: uint8/uint16/uint32 array of bit patterns; returns the converted bit patterns."""
     src = np.ascontiguousarray(src)
-    ss = {"F32": 4, "F16": 2, "BF16": 2}.get(src_dtype, src.itemsize)
-    ds = {"F32": 4, "F16": 2, "BF16": 2}.get(dst_dtype, ss)
+    ss = {"F64": 8, "F32": 4, "F16": 2, "BF16": 2}.get(src_dtype, src.itemsize)
+    ds = {"F64": 8, "F32": 4, "F16": 2, "BF16": 2}.get(dst_dtype, ss)
     n = src.nbytes // ss
     out = np.empty(n * ds, np.uint8)
     rc = lib().orc_cast_array(src.ctypes.data, n, dtype_id(src_dtype), dtype_id(dst_dtype), out.ctypes.data)

@@ -156,12 +156,94 @@ def test_nan_properties():
     assert np.array_equal(n & 0x1FF, ((x >> 13) & 0x1FF).astype(np.uint16))
 
 
+def _f64_samples():
+    """binary64 inputs around everything binary32 rounding can meet: every 1021st binary32 value
+    widened exactly, its exact midpoint to the next binary32 value (a tie) and the neighbours of that
+    midpoint and of the value itself; random patterns; the binary32 subnormal zone with its ties (odd
+    multiples of 2^-150); the overflow zone."""
+    rng = np.random.default_rng(3)
+    b = np.arange(0, 1 << 32, 1021, dtype=np.uint64).astype(np.uint32)
+    b = b[(b & 0x7FFFFFFF) < 0x7F800000]
+    w = b.view(np.float32).astype(np.float64).view(np.uint64)          # exact widening by numpy
+    parts = [w, w + np.uint64(1 << 28), w + np.uint64((1 << 28) - 1), w + np.uint64((1 << 28) + 1),
+             w + np.uint64(1), w - np.uint64(1)]
+    parts.append(rng.integers(0, 1 << 64, 2_000_000, dtype=np.uint64))
+    e = rng.integers(860, 900, 1_000_000, dtype=np.uint64)
+    m = rng.integers(0, 1 << 52, 1_000_000, dtype=np.uint64)
+    z = (e << np.uint64(52)) | m
+    parts += [z, z | np.uint64(1 << 63)]
+    parts.append((np.arange(1, 1 << 19, dtype=np.uint64).astype(np.float64) * 2.0 ** -150).view(np.uint64))
+    e = rng.integers(1023 + 120, 1023 + 130, 300_000, dtype=np.uint64)
+    m = rng.integers(0, 1 << 52, 300_000, dtype=np.uint64)
+    parts.append((e << np.uint64(52)) | m)
+    return np.concatenate(parts)
+
+
+def test_f64_to_f32_vs_numpy():
+    d = _f64_samples()
+    got = orc.cast_array(d, "F64", "F32")
+    with np.errstate(over="ignore", invalid="ignore"):
+        ref = d.view(np.float64).astype(np.float32).view(np.uint32)
+    ok = (d & np.uint64(0x7FFFFFFFFFFFFFFF)) <= np.uint64(0x7FF0000000000000)
+    assert np.array_equal(got[ok], ref[ok])
+    # and against torch, a second library
+    ref2 = torch.from_numpy(d.view(np.float64)).to(torch.float32).view(torch.int32).numpy().view(np.uint32)
+    assert np.array_equal(got[ok], ref2[ok])
+
+
+def test_f32_to_f64_vs_numpy_and_back():
+    x = np.concatenate([_f32_samples(), np.arange(0, 0x01000000, 7, dtype=np.uint32)])       # plus many subnormals
+    got = orc.cast_array(x, "F32", "F64")
+    with np.errstate(invalid="ignore"):
+        ref = x.view(np.float32).astype(np.float64).view(np.uint64)
+    ok = (x & 0x7FFFFFFF) <= 0x7F800000
+    assert np.array_equal(got[ok], ref[ok])
+    assert np.array_equal(orc.cast_array(got[ok], "F64", "F32"), x[ok])     # widening is exact
+
+
+def test_f64_constants_and_nan():
+    """binary64 <-> binary32 values fixed by IEEE-754, typed by hand."""
+    n = lambda v: int(orc.cast_array(np.array([v], np.uint64), "F64", "F32")[0])
+    w = lambda v: int(orc.cast_array(np.array([v], np.uint32), "F32", "F64")[0])
+    assert w(0x3F800000) == 0x3FF0000000000000                     # 1.0
+    assert w(0x00000001) == 0x36A0000000000000                     # 2^-149
+    assert w(0x007FFFFF) == 0x380FFFFFC0000000                     # largest subnormal
+    assert w(0x7F7FFFFF) == 0x47EFFFFFE0000000                     # largest finite
+    assert w(0xFF800000) == 0xFFF0000000000000 and w(0x80000000) == 0x8000000000000000
+    assert n(0x3FF0000000000000) == 0x3F800000
+    assert n(0x3FF0000010000000) == 0x3F800000                     # 1 + 2^-24: tie -> even (down)
+    assert n(0x3FF0000030000000) == 0x3F800002                     # 1 + 3*2^-24: tie -> even (up)
+    assert n(0x3FF0000010000001) == 0x3F800001
+    assert n(0x47EFFFFFEFFFFFFF) == 0x7F7FFFFF                     # just below the midpoint to 2^128
+    assert n(0x47EFFFFFF0000000) == 0x7F800000                     # the midpoint: tie -> even = infinity
+    assert n(0x47F0000000000000) == 0x7F800000                     # 2^128
+    assert n(0x36A0000000000000) == 0x00000001                     # 2^-149
+    assert n(0x3690000000000000) == 0x00000000                     # 2^-150: tie between 0 and 2^-149 -> 0
+    assert n(0x3690000000000001) == 0x00000001
+    assert n(0x36A8000000000000) == 0x00000002                     # 1.5 * 2^-149: tie -> even (2)
+    assert n(0x380FFFFFE0000000) == 0x00800000                     # (2^24 - 1) * 2^-150: tie -> smallest normal
+    assert n(0xB690000000000001) == 0x80000001 and n(0x0000000000000001) == 0 and n(0x8000000000000001) == 0x80000000
+    rng = np.random.default_rng(4)
+    d = rng.integers(0, 1 << 64, 100000, dtype=np.uint64) | np.uint64(0x7FF0000000000000)
+    d = d[(d & np.uint64(0xFFFFFFFFFFFFF)) != 0]
+    f = orc.cast_array(d, "F64", "F32")
+    assert np.all((f & 0x7FC00000) == 0x7FC00000) and np.array_equal(f >> 31, (d >> np.uint64(63)).astype(np.uint32))
+    assert np.array_equal(f & 0x3FFFFF, ((d >> np.uint64(29)) & np.uint64(0x3FFFFF)).astype(np.uint32))
+    x = rng.integers(0, 1 << 32, 100000, dtype=np.uint64).astype(np.uint32) | np.uint32(0x7F800000)
+    x = x[(x & 0x7FFFFF) != 0]
+    g = orc.cast_array(x, "F32", "F64")
+    assert np.all((g & np.uint64(0x7FF8000000000000)) == np.uint64(0x7FF8000000000000))
+    assert np.array_equal((g >> np.uint64(63)).astype(np.uint32), x >> 31)
+    assert np.array_equal(((g >> np.uint64(29)) & np.uint64(0x3FFFFF)).astype(np.uint32), x & 0x3FFFFF)
+    assert np.all((g & np.uint64(0x1FFFFFFF)) == 0)
+
+
 def test_identity_and_unsupported():
     x = np.arange(256, dtype=np.uint8)
     for dt in ("BOOL", "U8", "I8", "F8_E5M2", "F8_E4M3"):
         assert np.array_equal(orc.cast_array(x, dt, dt), x)
     assert np.array_equal(orc.cast_array(ALL16, "F16", "F16"), ALL16)     # NaN payloads untouched
-    for s, d in (("I16", "F16"), ("F32", "F64"), ("F64", "F32"), ("U8", "BOOL"), ("F8_E5M2", "F16")):
+    for s, d in (("I16", "F16"), ("F16", "F64"), ("F64", "BF16"), ("U8", "BOOL"), ("F8_E5M2", "F16"), ("I64", "F64")):
         with pytest.raises(orc.OracleError) as e:
             orc.cast_array(np.zeros(8, np.uint8), s, d)
         assert e.value.kind == "CAST"
