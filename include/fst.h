@@ -46,7 +46,7 @@ typedef enum fst_status {
     FST_E_DUP_NAME = -8,       /* a key twice in one file, or one name in two files */
     FST_E_NOT_FOUND = -9,      /* requested name is in no file */
     FST_E_SHARD = -10,         /* bad shard dim / rank / world / blocks, or dim not divisible */
-    FST_E_CAST = -11,          /* conversion outside {F32, F16, BF16} */
+    FST_E_CAST = -11,          /* conversion other than among {F32, F16, BF16} or F64 <-> F32 */
     FST_E_ALIGN = -12,         /* a pointer or base offset misses its required alignment */
     FST_E_RANGE = -13,         /* too many dims, buffer too small, index out of range */
     FST_E_HIP = -14,           /* a HIP runtime call failed */

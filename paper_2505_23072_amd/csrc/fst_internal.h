@@ -37,15 +37,19 @@ struct fst_header {
 namespace fst {
 
 // How a descriptor's rows are moved.  The vector path moves whole chunks (16 bytes when nothing
-// is converted, 8 elements otherwise) of rows that are a whole number of chunks.  The spliced path
+// is converted, 8 elements otherwise, 4 when binary64 is involved) of rows that are a whole number
+// of chunks.  The spliced path
 // serves rows that are not: its chunks are cut from the output stream, so a chunk may take its
 // first units from the end of one row and the rest from the start of the next.  The element path
 // moves single elements: tails shorter than a chunk, rows shorter than a chunk, and pieces whose
 // first output byte is not 16-byte aligned.
 enum Path : uint32_t { PATH_VEC = 0, PATH_ELEM = 1, PATH_SPLICE = 2 };
 
-// Conversion kinds (Section III-B).  COPY moves bytes and ignores the element type.
-enum Conv : uint32_t { CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CONV_F2H, CONV_F2B, CONV_COUNT };
+// Conversion kinds (Section III-B).  COPY moves bytes and ignores the element type.  H = binary16,
+// B = bfloat16, F = binary32, D = binary64.
+enum Conv : uint32_t {
+    CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CONV_F2H, CONV_F2B, CONV_D2F, CONV_F2D, CONV_COUNT
+};
 
 // One unit of kernel work, as uploaded to the device (64 bytes).
 struct DevDesc {
@@ -141,7 +145,7 @@ constexpr uint64_t SPLICE_PIECE_MAX_UNITS = (1ull << 31) - 64;
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
 uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)
 uint32_t conv_dst_bytes(uint32_t conv);
-uint32_t conv_chunk_elems(uint32_t conv);                     // 16 (bytes) for COPY, 8 otherwise
+uint32_t conv_chunk_elems(uint32_t conv);                     // 16 (bytes) for COPY, 4 with binary64, 8 otherwise
 
 // One kernel launch: pieces [first, first+count) of a device table, all of one launch class, with
 // their hint entries [hint_first, ...).

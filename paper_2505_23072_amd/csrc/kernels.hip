@@ -150,14 +150,52 @@ __device__ __forceinline__ uint32_t float_to_half(uint32_t x)
     return sign | r;
 }
 
+// binary32 -> binary64 (exact).  Subnormals: the 23-bit field m stands for m * 2^-149; the
+// integer is exact in binary64 and so is the scaling by a power of two.
+__device__ __forceinline__ uint64_t float_to_double(uint32_t x)
+{
+    const uint64_t sign = uint64_t(x >> 31) << 63;
+    const uint32_t mag = x & 0x7FFFFFFFu;
+    uint64_t r = (uint64_t(mag) << 29) + 0x3800000000000000ull;         // normal: rebias 127 -> 1023
+    if (mag < 0x00800000u) r = uint64_t(__double_as_longlong(double(mag) * 0x1p-149));
+    if (mag >= 0x7F800000u)
+        r = (uint64_t(mag) << 29) | 0x7FF0000000000000ull | ((mag & 0x7FFFFFu) ? 0x0008000000000000ull : 0ull);
+    return sign | r;
+}
+
+// binary64 -> binary32.
+__device__ __forceinline__ uint32_t double_to_float(uint64_t x)
+{
+    const uint32_t sign = uint32_t(x >> 32) & 0x80000000u;
+    const uint64_t mag = x & 0x7FFFFFFFFFFFFFFFull;
+    uint32_t r;
+    if (mag > 0x7FF0000000000000ull) {
+        r = 0x7FC00000u | uint32_t((mag >> 29) & 0x3FFFFFu);                   // NaN: quiet, leading payload kept
+    } else if (mag >= 0x47F0000000000000ull) {
+        r = 0x7F800000u;                                                        // 2^128 and above (and infinity)
+    } else if (mag >= 0x3810000000000000ull) {
+        // normal result: rebias, round the 29 dropped bits; a carry may reach infinity
+        const uint64_t t = mag - 0x3800000000000000ull;
+        r = uint32_t((t + 0x0FFFFFFFull + ((t >> 29) & 1ull)) >> 29);
+    } else {
+        // |x| < 2^-126: adding 2^-97 lines the value up so that the sum's low mantissa bits are
+        // |x| / 2^-149 rounded to nearest even by the adder itself (ulp of [2^-97, 2^-96) is 2^-149)
+        r = uint32_t(uint64_t(__double_as_longlong(__longlong_as_double((long long)mag) + 0x1p-97)) - 0x39E0000000000000ull);
+    }
+    return sign | r;
+}
+
 template <uint32_t CONV> struct ConvTraits;
-template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16; };
-template <> struct ConvTraits<CONV_H2B> { static constexpr uint32_t SRC = 16, DST = 16; };
-template <> struct ConvTraits<CONV_B2H> { static constexpr uint32_t SRC = 16, DST = 16; };
-template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 16, DST = 32; };
-template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 16, DST = 32; };
-template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DST = 16; };
-template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16; };
+// SRC / DST: bytes of one chunk before and after; UNITS: units per chunk (bytes when copying).
+template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 16; };
+template <> struct ConvTraits<CONV_H2B> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_B2H> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 8; };
+template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 8; };
+template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_D2F> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 4; };
+template <> struct ConvTraits<CONV_F2D> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 4; };
 
 template <uint32_t CONV>
 __device__ __forceinline__ uint32_t convert_bits(uint32_t v)
@@ -169,6 +207,15 @@ __device__ __forceinline__ uint32_t convert_bits(uint32_t v)
     if (CONV == CONV_F2H) return float_to_half(v);
     if (CONV == CONV_F2B) return float_to_bfloat(v);
     return v;
+}
+
+// One element of any width (the element path).
+template <uint32_t CONV>
+__device__ __forceinline__ uint64_t convert_element(uint64_t v)
+{
+    if (CONV == CONV_D2F) return double_to_float(v);
+    if (CONV == CONV_F2D) return float_to_double(uint32_t(v));
+    return convert_bits<CONV>(uint32_t(v));
 }
 
 template <uint32_t CONV>
@@ -205,6 +252,10 @@ __device__ __forceinline__ f32x2 float_pair(uint32_t a, uint32_t b)
     f.y = __uint_as_float(b);
     return f;
 }
+__device__ __forceinline__ double double_of(uint32_t lo, uint32_t hi)
+{
+    return __longlong_as_double((long long)(uint64_t(lo) | (uint64_t(hi) << 32)));
+}
 __device__ __forceinline__ uint32_t narrow_to_bfloat_pair(f32x2 f)
 {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
@@ -220,12 +271,19 @@ __device__ __forceinline__ uint32_t narrow_to_half_pair(f32x2 f)
 template <uint32_t CONV>
 __device__ __forceinline__ bool chunk_has_inf_or_nan(const Chunk32 &in)
 {
-    constexpr bool WIDE = CONV == CONV_F2H || CONV == CONV_F2B;
+    if (CONV == CONV_D2F) {
+        // the exponent of a binary64 element sits in its upper word
+        constexpr uint32_t MASK = 0x7FF00000u, LOW = 0x00100000u;
+        const uint32_t acc = ((in.lo.y & MASK) + LOW) | ((in.lo.w & MASK) + LOW) | ((in.hi.y & MASK) + LOW) |
+                             ((in.hi.w & MASK) + LOW);
+        return (acc & 0x80000000u) != 0;
+    }
+    constexpr bool WIDE = CONV == CONV_F2H || CONV == CONV_F2B || CONV == CONV_F2D;
     constexpr uint32_t MASK = WIDE ? 0x7F800000u : CONV == CONV_B2H ? 0x7F807F80u : 0x7C007C00u;
     constexpr uint32_t LOW = WIDE ? 0x00800000u : CONV == CONV_B2H ? 0x00800080u : 0x04000400u;
     uint32_t acc = ((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW) | ((in.lo.z & MASK) + LOW) |
                    ((in.lo.w & MASK) + LOW);
-    if (WIDE)
+    if (ConvTraits<CONV>::SRC == 32)
         acc |= ((in.hi.x & MASK) + LOW) | ((in.hi.y & MASK) + LOW) | ((in.hi.z & MASK) + LOW) |
                ((in.hi.w & MASK) + LOW);
     return (acc & 0x80008000u) != 0;
@@ -262,6 +320,18 @@ __device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
         o.lo.y = narrow_to_bfloat_pair(float_pair(in.lo.z, in.lo.w));
         o.lo.z = narrow_to_bfloat_pair(float_pair(in.hi.x, in.hi.y));
         o.lo.w = narrow_to_bfloat_pair(float_pair(in.hi.z, in.hi.w));
+    } else if (CONV == CONV_D2F) {
+        o.lo.x = __float_as_uint(float(double_of(in.lo.x, in.lo.y)));
+        o.lo.y = __float_as_uint(float(double_of(in.lo.z, in.lo.w)));
+        o.lo.z = __float_as_uint(float(double_of(in.hi.x, in.hi.y)));
+        o.lo.w = __float_as_uint(float(double_of(in.hi.z, in.hi.w)));
+    } else if (CONV == CONV_F2D) {
+        const uint64_t a = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.x))));
+        const uint64_t b = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.y))));
+        const uint64_t c = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.z))));
+        const uint64_t d = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.w))));
+        o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
+        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     }
     return o;
 }
@@ -290,6 +360,16 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
         o.hi.y = convert_bits<CONV>(in.lo.z >> 16);
         o.hi.z = convert_bits<CONV>(in.lo.w & 0xFFFFu);
         o.hi.w = convert_bits<CONV>(in.lo.w >> 16);
+    } else if (CONV == CONV_D2F) {
+        o.lo.x = double_to_float(in.lo.x | (uint64_t(in.lo.y) << 32));
+        o.lo.y = double_to_float(in.lo.z | (uint64_t(in.lo.w) << 32));
+        o.lo.z = double_to_float(in.hi.x | (uint64_t(in.hi.y) << 32));
+        o.lo.w = double_to_float(in.hi.z | (uint64_t(in.hi.w) << 32));
+    } else if (CONV == CONV_F2D) {
+        const uint64_t a = float_to_double(in.lo.x), b = float_to_double(in.lo.y);
+        const uint64_t c = float_to_double(in.lo.z), d = float_to_double(in.lo.w);
+        o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
+        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     } else {
         o.lo.x = convert_bits<CONV>(in.lo.x) | (convert_bits<CONV>(in.lo.y) << 16);
         o.lo.y = convert_bits<CONV>(in.lo.z) | (convert_bits<CONV>(in.lo.w) << 16);
@@ -428,7 +508,7 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const De
                                                                         const uint8_t *__restrict__ raw)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
-    constexpr uint32_t CH = CONV == CONV_COPY ? 16 : 8;                 // units per chunk
+    constexpr uint32_t CH = ConvTraits<CONV>::UNITS;                    // units per chunk
     constexpr uint32_t US = CS / CH;                                    // source bytes per unit
     const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
     const PieceRegs d = find_piece(descs, hints, b);
@@ -465,8 +545,8 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
                                                                        const uint32_t *__restrict__ hints,
                                                                        const uint8_t *__restrict__ raw)
 {
-    constexpr uint32_t ES = CONV == CONV_COPY ? 1 : (CONV == CONV_F2H || CONV == CONV_F2B) ? 4 : 2;
-    constexpr uint32_t ED = CONV == CONV_COPY ? 1 : (CONV == CONV_H2F || CONV == CONV_B2F) ? 4 : 2;
+    constexpr uint32_t ES = ConvTraits<CONV>::SRC / ConvTraits<CONV>::UNITS;         // bytes per source element
+    constexpr uint32_t ED = ConvTraits<CONV>::DST / ConvTraits<CONV>::UNITS;
     const uint32_t b = blockIdx.x;
     const PieceRegs d = find_piece(descs, hints, b);
     const uint32_t t = b - d.tile0();
@@ -482,14 +562,15 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
         const uint64_t cc = uint64_t(col0) + i;
         const uint64_t r = cc / upr;
         const uint8_t *s = src + r * stride + (cc - r * upr) * ES;
-        uint32_t v = 0;
+        uint64_t v = 0;
 #pragma unroll
-        for (uint32_t k = 0; k < ES; ++k) v |= uint32_t(*(const FST_GLOBAL uint8_t *)(s + k)) << (8 * k);
-        v = convert_bits<CONV>(v);
+        for (uint32_t k = 0; k < ES; ++k) v |= uint64_t(*(const FST_GLOBAL uint8_t *)(s + k)) << (8 * k);
+        v = convert_element<CONV>(v);
         uint8_t *o = dst + uint64_t(i) * ED;
         if (ED == 1) *(FST_GLOBAL uint8_t *)(o) = uint8_t(v);
         else if (ED == 2) *(FST_GLOBAL uint16_t *)(o) = uint16_t(v);
-        else *(FST_GLOBAL uint32_t *)(o) = v;
+        else if (ED == 4) *(FST_GLOBAL uint32_t *)(o) = uint32_t(v);
+        else *(FST_GLOBAL uint64_t *)(o) = v;
     }
 }
 
@@ -531,6 +612,8 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
     case CONV_B2F: return launch_conv<CONV_B2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
     case CONV_F2H: return launch_conv<CONV_F2H>(variant, descs_dev, hints_dev, n_tiles, raw, s);
     case CONV_F2B: return launch_conv<CONV_F2B>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_D2F: return launch_conv<CONV_D2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2D: return launch_conv<CONV_F2D>(variant, descs_dev, hints_dev, n_tiles, raw, s);
     default: return fail(FST_E_ARG, "unknown launch class %u", cls);
     }
 }

@@ -20,18 +20,20 @@ uint32_t conv_kind(int s, int d)
     if (s == FST_BF16 && d == FST_F32) return CONV_B2F;
     if (s == FST_F32 && d == FST_F16) return CONV_F2H;
     if (s == FST_F32 && d == FST_BF16) return CONV_F2B;
+    if (s == FST_F64 && d == FST_F32) return CONV_D2F;
+    if (s == FST_F32 && d == FST_F64) return CONV_F2D;
     return CONV_COUNT;
 }
 
 uint32_t conv_src_bytes(uint32_t c)
 {
-    return c == CONV_COPY ? 1 : (c == CONV_F2H || c == CONV_F2B) ? 4 : 2;
+    return c == CONV_COPY ? 1 : c == CONV_D2F ? 8 : (c == CONV_F2H || c == CONV_F2B || c == CONV_F2D) ? 4 : 2;
 }
 uint32_t conv_dst_bytes(uint32_t c)
 {
-    return c == CONV_COPY ? 1 : (c == CONV_H2F || c == CONV_B2F) ? 4 : 2;
+    return c == CONV_COPY ? 1 : c == CONV_F2D ? 8 : (c == CONV_H2F || c == CONV_B2F || c == CONV_D2F) ? 4 : 2;
 }
-uint32_t conv_chunk_elems(uint32_t c) { return c == CONV_COPY ? 16 : 8; }
+uint32_t conv_chunk_elems(uint32_t c) { return c == CONV_COPY ? 16 : (c == CONV_D2F || c == CONV_F2D) ? 4 : 8; }
 
 namespace {
 

@@ -8,7 +8,7 @@ from oracle import oracle as orc
 from paper_2505_23072_amd import binding as B
 from paper_2505_23072_amd import device
 from synth import writer
-from util_cases import FLOATS, make_file, random_bits, random_request
+from util_cases import FLOATS, cast_targets, make_file, random_bits, random_request
 from util_gpu import (first_diff, headers_of, materialize_resident, materialize_slots, oracle_outputs,
                       upload_resident)
 
@@ -55,14 +55,13 @@ def test_every_source_alignment(residue):
     """Body start at every residue mod 16, with an odd-sized tensor in front to shift the rest by one."""
     rng = np.random.default_rng(residue)
     ts = [("pad", "U8", (residue % 3,), random_bits(rng, "U8", (residue % 3,)).tobytes())]
-    for dt in ("BF16", "F16", "F32", "I8", "I64"):
+    for dt in ("BF16", "F16", "F32", "F64", "I8", "I64"):
         ts.append((f"w.{dt}", dt, SHAPE, random_bits(rng, dt, SHAPE).tobytes()))
         ts.append((f"v.{dt}", dt, (1031,), random_bits(rng, dt, (1031,)).tobytes()))
     blob = writer.write_file(None, ts, None, residue)
     names, reqs = [], []
     for n, dt, shape, _ in ts[1:]:
-        dsts = [None] + ([d for d in FLOATS if d != dt] if dt in FLOATS else [])
-        for dst in dsts:
+        for dst in [None] + cast_targets(dt):
             for dim, blocks in ((-1, 1), (0, 1), (1, 1)) if len(shape) == 2 else ((-1, 1),):
                 names.append(n)
                 reqs.append((dst, dim, blocks))
@@ -142,7 +141,7 @@ def test_ragged_rows_of_at_least_one_chunk(residue):
     rng = np.random.default_rng(300 + residue)
     spec = [("a", "BF16", (300, 1096), 8), ("b", "F32", (200, 44), 4), ("c", "I8", (300, 100), 4),
             ("d", "F16", (129, 72), 8), ("e", "BF16", (6, 50, 21), 5), ("f", "BF16", (4099, 1100), 4),
-            ("g", "F32", (1031, 72), 8)]
+            ("g", "F32", (1031, 72), 8), ("h", "F64", (300, 44), 4), ("i", "F64", (129, 40), 8)]
     ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
     ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
     ts.append(("qkv", "BF16", (120, 37), random_bits(rng, "BF16", (120, 37)).tobytes()))
@@ -152,7 +151,7 @@ def test_ragged_rows_of_at_least_one_chunk(residue):
         for n, dt, shape, w in spec:
             if w != world:
                 continue
-            for dst in [None] + ([d for d in FLOATS if d != dt] if dt in FLOATS else []):
+            for dst in [None] + cast_targets(dt):
                 names.append(n)
                 reqs.append((dst, 1, 1))
         if world == 4:
@@ -194,6 +193,35 @@ def test_f32_conversions_on_device(dst):
         got, _ = materialize_resident([blob], ["x"], [(dst, -1, 1)])
         want = orc.cast_array(x, "F32", dst).tobytes()
         assert got[0] == want, f"F32->{dst} lead {lead}: {first_diff(got[0], want)}"
+
+
+def test_binary64_conversions_on_device():
+    """binary64 -> binary32 on inputs around everything the rounding can meet (every 509th binary32 value
+    widened, its midpoints to the neighbours and the values next to those, the subnormal zone with its
+    ties, the overflow zone, random patterns with NaNs), and binary32 -> binary64 on a stride of all
+    binary32 patterns plus all subnormals; sources at an aligned and at an odd offset."""
+    rng = np.random.default_rng(6)
+    b = np.arange(0, 1 << 32, 509, dtype=np.uint64).astype(np.uint32)
+    w = orc.cast_array(b[(b & 0x7FFFFFFF) < 0x7F800000], "F32", "F64")
+    parts = [w, w + np.uint64(1 << 28), w + np.uint64((1 << 28) - 1), w + np.uint64((1 << 28) + 1), w + np.uint64(1),
+             w - np.uint64(1), rng.integers(0, 1 << 64, 3_000_000, dtype=np.uint64)]
+    e = rng.integers(860, 900, 1_000_000, dtype=np.uint64)
+    z = (e << np.uint64(52)) | rng.integers(0, 1 << 52, 1_000_000, dtype=np.uint64)
+    parts += [z, z | np.uint64(1 << 63), (np.arange(1, 1 << 20, dtype=np.uint64) << np.uint64(28)) + np.uint64(0x3690000000000000)]
+    e = rng.integers(1023 + 120, 1023 + 130, 300_000, dtype=np.uint64)
+    parts.append((e << np.uint64(52)) | rng.integers(0, 1 << 52, 300_000, dtype=np.uint64))
+    d = np.concatenate(parts)
+    x = np.concatenate([np.arange(0, 1 << 32, 61, dtype=np.uint64).astype(np.uint32), np.arange(0, 0x00800000, dtype=np.uint32),
+                        np.arange(0x7F000000, 0x80000000, 5, dtype=np.uint32)])
+    print(f"{len(d)} binary64 inputs, {len(x)} binary32 inputs", flush=True)
+    for lead in (0, 3):
+        ts = [("lead", "U8", (lead,), bytes(lead)), ("d", "F64", (len(d),), d.tobytes()), ("x", "F32", (len(x),), x.tobytes())]
+        blob = writer.write_file(None, ts, None, 0)
+        got, _ = materialize_resident([blob], ["d", "x"], [("F32", -1, 1), ("F64", -1, 1)])
+        want_d = orc.cast_array(d, "F64", "F32").tobytes()
+        want_x = orc.cast_array(x, "F32", "F64").tobytes()
+        assert got[0] == want_d, f"F64->F32 lead {lead}: {first_diff(got[0], want_d)}"
+        assert got[1] == want_x, f"F32->F64 lead {lead}: {first_diff(got[1], want_x)}"
 
 
 @pytest.mark.parametrize("dst", ["BF16", "F16"])

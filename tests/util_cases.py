@@ -11,6 +11,15 @@ ES = {k: np.dtype(v).itemsize for k, v in NP.items()}
 FLOATS = ("F32", "F16", "BF16")
 
 
+def cast_targets(dtype):
+    """The element types a stored dtype can be converted to (other than itself)."""
+    if dtype == "F64":
+        return ["F32"]
+    if dtype == "F32":
+        return ["F16", "BF16", "F64"]
+    return [d for d in FLOATS if d != dtype] if dtype in FLOATS else []
+
+
 def random_bits(rng, dtype, shape):
     """Random bit patterns (for floats: all exponents incl. NaN/inf/subnormal appear)."""
     n = int(np.prod(shape)) if len(shape) else 1
@@ -40,6 +49,8 @@ def random_request(rng, dtype, shape, world):
     dst = None
     if dtype in FLOATS and rng.random() < 0.6:
         dst = FLOATS[int(rng.integers(3))]
+    elif dtype in ("F32", "F64") and rng.random() < 0.5:
+        dst = "F64" if dtype == "F32" else "F32"
     dims = [d for d in range(len(shape)) if shape[d] % world == 0]
     if not dims or rng.random() < 0.25:
         return dst, -1, 1
