@@ -4,7 +4,8 @@
  *
  * Parity pins (tests/test_oracle_*.py): hand-built files whose bytes are written out in the test,
  * files written and read back by the independent `safetensors` package, numpy slicing for the
- * partitions, numpy float16 / torch bfloat16 conversions for every non-NaN input.  NaN payload
+ * partitions, hand-derived partitions and conversions of a hand-typed file, numpy float16 /
+ * float64 and torch bfloat16 / float32 conversions for every non-NaN input.  NaN payload
  * handling follows the written rule below and is pinned by properties only (sign, quiet bit,
  * leading payload bits): the libraries disagree with each other there -- library parity unpinned
  * for NaN payloads.
