@@ -300,6 +300,38 @@ def test_on_a_side_stream_and_empty_plan():
     got, plan = materialize_resident([e], ["e", "f"], [(None, -1, 1), ("F32", -1, 1)])
     assert got == [b"", b""] and plan.group_count() == 0
 
+def test_degenerate_requests():
+    """The corners of the request space: eight dimensions split on the first, a middle and the last one;
+    as many ranks as the dimension has indices; one rank (the share is the whole tensor) with and without
+    blocks; tensors with a zero dimension, split or not; scalars; a one-element tensor."""
+    rng = np.random.default_rng(31)
+    t8 = (2, 3, 2, 4, 2, 3, 2, 8)
+    ts = [("lead", "U8", (1,), b"\x07"),
+          ("t8", "BF16", t8, random_bits(rng, "BF16", t8).tobytes()),
+          ("m", "F32", (12, 40), random_bits(rng, "F32", (12, 40)).tobytes()),
+          ("z0", "F16", (0, 16), b""), ("z1", "F16", (16, 0), b""), ("z2", "I32", (4, 0, 8), b""),
+          ("s", "F32", (), random_bits(rng, "F32", ()).tobytes()),
+          ("one", "BF16", (1,), random_bits(rng, "BF16", (1,)).tobytes()),
+          ("one2", "F64", (1, 1), random_bits(rng, "F64", (1, 1)).tobytes())]
+    blob = writer.write_file(None, ts, None, 11)
+    cases = [
+        (2, 1, ["t8", "t8", "t8", "t8"], [(None, 0, 1), ("F16", 2, 1), ("F32", 4, 1), (None, 6, 1)]),
+        (4, 3, ["t8", "t8"], [(None, 3, 1), ("F32", 7, 1)]),
+        (8, 7, ["t8", "m"], [("F16", 7, 1), ("F64", 1, 1)]),                      # one index of dim 7 per rank
+        (12, 11, ["m", "m"], [(None, 0, 1), ("BF16", 0, 1)]),                     # one row per rank
+        (1, 0, ["m", "m", "m", "t8"], [(None, 0, 1), ("F16", 1, 1), (None, 0, 3), ("F32", 0, 2)]),   # one rank
+        (4, 2, ["z0", "z1", "z1", "z2", "z2", "s", "one", "one2"],
+         [(None, 1, 1), ("F32", 0, 1), (None, -1, 1), (None, 0, 1), (None, 2, 1), ("BF16", -1, 1), ("F32", -1, 1), ("F32", -1, 1)]),
+    ]
+    for world, rank, names, reqs in cases:
+        print(f"world {world} rank {rank}: {list(zip(names, reqs))}", flush=True)
+        want = oracle_outputs([blob], names, reqs, rank, world)
+        got, plan = materialize_resident([blob], names, reqs, rank, world)
+        _check(got, want, names, reqs, f"world {world} rank {rank}")
+        got, _ = materialize_slots([blob], names, reqs, rank, world, 4096)
+        _check(got, want, names, reqs, f"slots world {world} rank {rank}")
+
+
 def test_prepare_once_launch_on_two_source_buffers():
     """The table is uploaded once; the kernels are then launched on two raw buffers of the same layout
     and different content, and once more per group after re-preparing group by group."""
