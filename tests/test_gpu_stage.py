@@ -211,6 +211,64 @@ def test_loader_api(tmp_path):
     sh.close()
 
 
+def test_files_written_by_the_safetensors_package(tmp_path):
+    """Interoperation with the format's own implementation: checkpoints written by the `safetensors`
+    package (its header sizes, key order and padding, whatever they are) are loaded through the staging
+    ring and the kernels and must equal, bit for bit, what the package's own loader returns; slices and
+    conversions are compared with torch indexing / torch CPU conversions of the package's tensors."""
+    import safetensors.torch as st
+    from paper_2505_23072_amd.loader import LocalShard, SafeTensorsFileLoader, SingleGroup
+    g = torch.Generator().manual_seed(5)
+    files = {}
+    for f in range(2):
+        files[f] = {
+            f"l{f}.q.weight": (torch.randn(96, 64, generator=g) * 0.02).to(torch.bfloat16),
+            f"l{f}.o.weight": (torch.randn(64, 96, generator=g) * 0.02).to(torch.float16),
+            f"l{f}.norm.weight": torch.ones(64, dtype=torch.float32),
+            f"l{f}.ids": torch.arange(37, dtype=torch.int64),
+            f"l{f}.mask": torch.arange(13) % 2 == 0,
+            f"l{f}.bytes": torch.arange(7, dtype=torch.uint8),
+            f"l{f}.scalar": torch.tensor(3.25, dtype=torch.float64),
+        }
+    paths = []
+    for f, tensors in files.items():
+        p = str(tmp_path / f"pkg{f}.safetensors")
+        st.save_file(tensors, p, metadata={"format": "pt"} if f else None)
+        paths.append(p)
+    ref = {}
+    for p in paths:
+        ref.update(st.load_file(p))          # the package's own loader, on the CPU
+
+    def bits(t):
+        return t.contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes() if t.numel() else b""
+
+    loader = SafeTensorsFileLoader(SingleGroup(), torch.device("cuda:0"))
+    loader.add_filenames({0: paths})
+    fb = loader.copy_files_to_device()
+    assert sorted(fb.keys()) == sorted(ref)
+    for k, want in ref.items():
+        got = fb.get_tensor(k)
+        assert got.dtype == want.dtype and tuple(got.shape) == tuple(want.shape), k
+        assert bits(got) == bits(want), k
+    # conversions of finite values: torch's CPU conversion is a second opinion
+    assert bits(fb.get_tensor("l0.q.weight", "F16")) == bits(ref["l0.q.weight"].to(torch.float16))
+    assert bits(fb.get_tensor("l1.o.weight", "BF16")) == bits(ref["l1.o.weight"].to(torch.bfloat16))
+    assert bits(fb.get_tensor("l0.norm.weight", "F64")) == bits(ref["l0.norm.weight"].to(torch.float64))
+    assert bits(fb.get_tensor("l1.scalar", "F32")) == bits(ref["l1.scalar"].to(torch.float32))
+    fb.close()
+    loader.close()
+    sh = SafeTensorsFileLoader(LocalShard(2, 4), torch.device("cuda:0"))
+    sh.add_filenames({0: paths})
+    fb = sh.copy_files_to_device()
+    assert bits(fb.get_sharded("l1.q.weight", 0)) == bits(ref["l1.q.weight"][48:72])          # rows of rank 2 of 4
+    assert bits(fb.get_sharded("l0.o.weight", 1)) == bits(ref["l0.o.weight"][:, 48:72])       # columns of rank 2 of 4
+    assert bits(fb.get_sharded("l0.q.weight", 0, blocks=3)) == bits(torch.cat([ref["l0.q.weight"][b * 32 + 16:b * 32 + 24]
+                                                                              for b in range(3)]))
+    assert bits(fb.get_sharded("l1.o.weight", 1, "F32")) == bits(ref["l1.o.weight"][:, 48:72].to(torch.float32))
+    fb.close()
+    sh.close()
+
+
 def _specs_of(blobs):
     from oracle import oracle as orc
     out = []
