@@ -68,7 +68,7 @@ def _run_resident(spec, layers, group_bytes=GB):
     raw = device.device_bytes(raw_len)
     ws = device.device_bytes(plan.workspace_bytes())
     bufs, ptrs = device.alloc_outputs(plan)
-    st = B.Stager(16, 12, 32 << 20)
+    st = B.Stager(8, 12, 128 << 20)          # the ring bench.py uses
     try:
         stats = st.stage_resident(plan, model.read_fn, model.ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(), ws.numel())
     finally:
@@ -107,7 +107,7 @@ def _run_streamed(spec, layers, dev_slots, slot_bytes, min_gap=None):
     slots = [device.device_bytes(slot_bytes) for _ in range(dev_slots)]
     ws = device.device_bytes(plan.workspace_bytes())
     bufs, ptrs = device.alloc_outputs(plan)
-    st = B.Stager(16, 14, 32 << 20)
+    st = B.Stager(8, 12, 128 << 20)          # the ring bench.py uses
     try:
         stats = st.stage_streamed(plan, model.read_fn, model.ctx, [s.data_ptr() for s in slots], slot_bytes, ptrs,
                                   ws.data_ptr(), ws.numel())
