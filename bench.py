@@ -102,8 +102,7 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=12)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (one MI355X per box); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -71,8 +71,8 @@ int main()
     std::vector<const char *> cnames;
     for (const std::string &s : names) cnames.push_back(s.c_str());
 
-    for (int round = 0; round < 2; ++round) {
-        const bool streamed = round == 1;
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool streamed = pass == 1;
         std::vector<uint64_t> zero(files.size(), 0);
         fst_plan *plan = nullptr;
         CHECK(fst_plan_uniform(hdrs.data(), streamed ? zero.data() : bases.data(), files.size(), cnames.data(), cnames.size(),
