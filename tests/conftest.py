@@ -23,7 +23,7 @@ def _has_gpu() -> bool:
 def pytest_collection_modifyitems(config, items):
     if _has_gpu():
         return
-    skip = pytest.mark.skip(reason="no GPU in this container")
+    skip = pytest.mark.skip(reason="no GPU visible")
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
