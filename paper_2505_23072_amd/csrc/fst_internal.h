@@ -129,10 +129,10 @@ constexpr uint32_t ELEM_BLOCK_THREADS = 256;
 constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 // elements per tile
 inline uint32_t tile_units(uint32_t path) { return path == PATH_ELEM ? ELEM_TILE_UNITS : VEC_TILE_UNITS; }
 // Workgroups are dealt to the 8 XCDs round-robin.  The tile index is permuted so that each XCD
-// works on runs of XCD_RUN consecutive tiles (1 MiB of output), which measured faster than both
+// works on runs of XCD_RUN consecutive tiles (512 KiB of output), which measured faster than both
 // tile-by-tile interleaving and giving each XCD one contiguous eighth.
 constexpr uint32_t XCD_COUNT = 8;
-constexpr uint32_t XCD_RUN = 64;
+constexpr uint32_t XCD_RUN = 32;
 // A workgroup finds its piece through a hint table with one entry per HINT_SPAN tiles (the piece
 // that holds the span's first tile) plus a closing entry per launch (its last piece): the owner of
 // a tile lies between its span's entry and the next one; for large tensors the two coincide.
