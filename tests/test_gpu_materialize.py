@@ -300,6 +300,26 @@ def test_on_a_side_stream_and_empty_plan():
     got, plan = materialize_resident([e], ["e", "f"], [(None, -1, 1), ("F32", -1, 1)])
     assert got == [b"", b""] and plan.group_count() == 0
 
+def test_thousands_of_small_tensors():
+    """6000 tensors of 1 element .. 3 tiles, in four dtypes, a third of them converted: hint spans that hold
+    dozens of pieces each, in every launch class, found by the bounded binary search."""
+    rng = np.random.default_rng(55)
+    ts, names, reqs = [], [], []
+    for i in range(6000):
+        dt = ("U8", "BF16", "F16", "F32")[int(rng.integers(4))]
+        n = int(rng.integers(1, 2000)) if rng.random() < 0.9 else int(rng.integers(2000, 30000))
+        ts.append((f"t{i}", dt, (n,), random_bits(rng, dt, (n,)).tobytes()))
+        names.append(f"t{i}")
+        targets = cast_targets(dt)
+        reqs.append((targets[int(rng.integers(len(targets)))] if targets and rng.random() < 0.35 else None, -1, 1))
+    blob = writer.write_file(None, ts, None, 5)
+    want = oracle_outputs([blob], names, reqs)
+    got, plan = materialize_resident([blob], names, reqs)
+    _check(got, want, names, reqs, "one launch set")
+    got, _ = materialize_resident([blob], names, reqs, max_group_bytes=1 << 20, per_group=True)
+    _check(got, want, names, reqs, "groups of 1 MiB")
+
+
 def test_degenerate_requests():
     """The corners of the request space: eight dimensions split on the first, a middle and the last one;
     as many ranks as the dimension has indices; one rank (the share is the whole tensor) with and without
