@@ -118,13 +118,12 @@ inline uint32_t launch_class(const Piece &p)
 }
 
 // Geometry of the kernels, fixed at compile time and needed by the planner to count tiles.
-// The vector kernels run 1024-thread workgroups (16 wavefronts) in which every lane moves
-// VEC_UNROLL chunks: one tile = 1024 chunks = 16 KiB of 16-byte chunks.  One chunk per lane
-// measured fastest: many short-lived wavefronts keep more requests in flight than fewer
-// wavefronts with several loads each.
+// The vector and spliced kernels run 1024-thread workgroups (16 wavefronts) in which every lane
+// moves one chunk: one tile = 1024 chunks = 16 KiB of 16-byte chunks.  One chunk per lane measured
+// fastest: many short-lived wavefronts keep more requests in flight than fewer wavefronts with
+// several loads each.
 constexpr uint32_t VEC_BLOCK_THREADS = 1024;
-constexpr uint32_t VEC_UNROLL = 1;                       // chunks per thread
-constexpr uint32_t VEC_TILE_UNITS = VEC_BLOCK_THREADS * VEC_UNROLL;           // chunks per tile
+constexpr uint32_t VEC_TILE_UNITS = VEC_BLOCK_THREADS;                        // chunks per tile
 constexpr uint32_t ELEM_BLOCK_THREADS = 256;
 constexpr uint32_t ELEM_TILE_UNITS = ELEM_BLOCK_THREADS * 16;                 // elements per tile
 inline uint32_t tile_units(uint32_t path) { return path == PATH_ELEM ? ELEM_TILE_UNITS : VEC_TILE_UNITS; }

@@ -23,7 +23,6 @@ namespace fst {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));      // 16 bytes at a 4-byte aligned address
 // Everything the kernels touch is global memory; saying so keeps the compiler from emitting flat
 // (generic address space) accesses for pointers it cannot trace back to a kernel argument.
