@@ -119,10 +119,11 @@ void fst_header_free(fst_header *h);
 /* ---------------------------------------------------------------- plan
  *
  * A request asks for one named tensor as one rank sees it:
- *   dst_dtype  FST_KEEP, or F32/F16/BF16 when the stored type is one of those three
- *              (conversion in the same pass as the copy, Section III-B; round to nearest even).
- *   shard_dim  -1 = whole tensor; d >= 0 = the rank's equal share of dimension d
- *              (Section III-B: "partitioning tensors at a dimension to be the same shape").
+ *   dst_dtype  FST_KEEP, or a floating-point type other than the stored one: any pair among
+ *              F32, F16 and BF16, and F64 <-> F32 (conversion in the same pass as the copy,
+ *              Section III-B; one rounding, to nearest even).  Any other pair with differing
+ *              types: FST_E_CAST.
+ *   shard_dim  -1 = whole tensor; d >= 0 = the rank's equal share of dimension d (Section III-B).
  *              Column-wise split of an input projection = dim 0 of the stored [out, in] matrix,
  *              row-wise split of an output projection = dim 1 (Section II-A).
  *   blocks     1, or b > 1 with shard_dim 0: dimension 0 is b stacked sub-tensors (fused QKV);

@@ -5,7 +5,9 @@
  * Parity pins (tests/test_oracle_*.py): hand-built files whose bytes are written out in the test,
  * files written and read back by the independent `safetensors` package, numpy slicing for the
  * partitions, hand-derived partitions and conversions of a hand-typed file, numpy float16 /
- * float64 and torch bfloat16 / float32 conversions for every non-NaN input.  NaN payload
+ * float64 and torch bfloat16 / float32 conversions for every non-NaN input; binary64 -> 16-bit
+ * types against numpy's direct float64 -> float16 conversion, against round-half-even on exact
+ * rationals, and on inputs built a hair beside every tie (where rounding twice goes wrong).  NaN payload
  * handling follows the written rule below and is pinned by properties only (sign, quiet bit,
  * leading payload bits): the libraries disagree with each other there -- library parity unpinned
  * for NaN payloads.
@@ -607,15 +609,49 @@ uint32_t orc_f64_to_f32(uint64_t x)
     return s | (uint32_t)q;
 }
 
-static int is_float_dtype(int d) { return d == ORC_F32 || d == ORC_F16 || d == ORC_BF16; }
+/* binary64 -> a 16-bit format with `mb` stored mantissa bits and exponent bias `bias` (binary16:
+ * 10 and 15; bfloat16: 7 and 127), rounded ONCE from the 53-bit significand.  Going through
+ * binary32 would round twice and differ on values that the first rounding moves onto a tie. */
+static uint16_t f64_to_16bit(uint64_t x, int mb, int bias)
+{
+    uint16_t s = (uint16_t)((x >> 48) & 0x8000u);
+    uint64_t a = x & 0x7FFFFFFFFFFFFFFFull;
+    int64_t e = (int64_t)(a >> 52);
+    uint64_t m = a & 0xFFFFFFFFFFFFFull;
+    uint16_t inf = (uint16_t)(0x7FFFu & ~((1u << mb) - 1u));     /* exponent field all ones */
+    uint16_t quiet = (uint16_t)(1u << (mb - 1));
+    if (a > 0x7FF0000000000000ull) return (uint16_t)(s | inf | quiet | ((m >> (52 - mb)) & (quiet - 1u)));
+    int64_t E = e - 1023 + bias;                                 /* exponent field of a normal result */
+    if (E >= (inf >> mb)) return (uint16_t)(s | inf);            /* too large (and infinity) */
+    if (E >= 1) {                                                /* normal, or rounds up to infinity */
+        uint32_t r = (uint32_t)(E << mb) | (uint32_t)(m >> (52 - mb));
+        uint64_t rem = m & (((uint64_t)1 << (52 - mb)) - 1u), half = (uint64_t)1 << (51 - mb);
+        if (rem > half || (rem == half && (r & 1u))) r++;        /* a carry moves the exponent up */
+        return (uint16_t)(s | r);
+    }
+    /* subnormal result: q = round(value / 2^(1-bias-mb)), value = M * 2^(e-1075) */
+    int64_t sh = 1076 - e - bias - mb;                           /* at least 53 - mb */
+    if (e == 0 || sh > 54) return s;                             /* below half the smallest subnormal */
+    uint64_t M = m | 0x10000000000000ull;
+    uint64_t q = M >> sh;
+    uint64_t rem = M & (((uint64_t)1 << sh) - 1u);
+    uint64_t half = (uint64_t)1 << (sh - 1);
+    if (rem > half || (rem == half && (q & 1u))) q++;
+    return (uint16_t)(s | q);
+}
 
-/* Conversions that exist: among F32, F16, BF16, and between F64 and F32 (a 16-bit type and F64
- * would need a single rounding from 53 bits, which going through binary32 does not give). */
+uint16_t orc_f64_to_f16(uint64_t x) { return f64_to_16bit(x, 10, 15); }
+uint16_t orc_f64_to_bf16(uint64_t x) { return f64_to_16bit(x, 7, 127); }
+/* 16-bit -> binary64: two exact widenings in a row. */
+uint64_t orc_f16_to_f64(uint16_t h) { return orc_f32_to_f64(orc_f16_to_f32(h)); }
+uint64_t orc_bf16_to_f64(uint16_t b) { return orc_f32_to_f64(orc_bf16_to_f32(b)); }
+
+static int is_float_dtype(int d) { return d == ORC_F64 || d == ORC_F32 || d == ORC_F16 || d == ORC_BF16; }
+
+/* Conversions that exist: among F64, F32, F16 and BF16. */
 static int can_convert(int sd, int dd)
 {
-    if (sd == dd) return 1;
-    if (is_float_dtype(sd) && is_float_dtype(dd)) return 1;
-    return (sd == ORC_F64 && dd == ORC_F32) || (sd == ORC_F32 && dd == ORC_F64);
+    return sd == dd || (is_float_dtype(sd) && is_float_dtype(dd));
 }
 
 static uint64_t load_le(const uint8_t *p, uint64_t es)
@@ -631,12 +667,13 @@ static void store_le(uint8_t *p, uint64_t es, uint64_t v)
 }
 
 /* One element.  Narrow-to-narrow goes through binary32, which holds every 16-bit value exactly,
- * so the result is rounded once. */
+ * so the result is rounded once; binary64 to a 16-bit type is rounded once from 53 bits. */
 static uint64_t convert(uint64_t v, int sd, int dd)
 {
     if (sd == dd) return v;
-    if (sd == ORC_F64) return orc_f64_to_f32(v);
-    if (dd == ORC_F64) return orc_f32_to_f64((uint32_t)v);
+    if (sd == ORC_F64) return dd == ORC_F32 ? orc_f64_to_f32(v) : dd == ORC_F16 ? orc_f64_to_f16(v) : orc_f64_to_bf16(v);
+    if (dd == ORC_F64)
+        return sd == ORC_F32 ? orc_f32_to_f64((uint32_t)v) : sd == ORC_F16 ? orc_f16_to_f64((uint16_t)v) : orc_bf16_to_f64((uint16_t)v);
     uint32_t f;
     if (sd == ORC_F32) f = (uint32_t)v;
     else if (sd == ORC_F16) f = orc_f16_to_f32((uint16_t)v);

@@ -90,6 +90,10 @@ uint16_t orc_f32_to_bf16(uint32_t x);
 uint16_t orc_f32_to_f16(uint32_t x);
 uint64_t orc_f32_to_f64(uint32_t x);
 uint32_t orc_f64_to_f32(uint64_t x);
+uint16_t orc_f64_to_f16(uint64_t x);      /* one rounding from 53 bits, not via binary32 */
+uint16_t orc_f64_to_bf16(uint64_t x);
+uint64_t orc_f16_to_f64(uint16_t h);      /* exact */
+uint64_t orc_bf16_to_f64(uint16_t b);
 /* n elements of src_dtype at src -> dst_dtype at dst. */
 int orc_cast_array(const uint8_t *src, uint64_t n, int src_dtype, int dst_dtype, uint8_t *dst);
 

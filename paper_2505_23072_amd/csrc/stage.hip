@@ -4,8 +4,9 @@
 //
 // Reader threads fill ring slots, several threads per slot (a block is read in parts, so a slot
 // is full after a fraction of the time one thread would need, while the copy out of it stays one
-// large transfer); the calling thread is the only one that talks to the GPU: it issues one
-// hipMemcpyAsync per filled slot on the copy stream, in block order, and as soon as
+// large transfer); the calling thread is the only one that enqueues GPU work (reader threads only
+// wait, with hipEventSynchronize, for the copy out of the ring slot they are about to refill): it
+// issues one hipMemcpyAsync per filled slot on the copy stream, in block order, and as soon as
 // the last block of a group is queued it makes the compute stream wait for that copy and queues
 // the group's kernels.  Kernels of group g therefore run while the bytes of group g+1 are still
 // crossing PCIe.  For checkpoints larger than device memory the raw buffer is itself a ring of

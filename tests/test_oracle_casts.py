@@ -243,7 +243,161 @@ def test_identity_and_unsupported():
     for dt in ("BOOL", "U8", "I8", "F8_E5M2", "F8_E4M3"):
         assert np.array_equal(orc.cast_array(x, dt, dt), x)
     assert np.array_equal(orc.cast_array(ALL16, "F16", "F16"), ALL16)     # NaN payloads untouched
-    for s, d in (("I16", "F16"), ("F16", "F64"), ("F64", "BF16"), ("U8", "BOOL"), ("F8_E5M2", "F16"), ("I64", "F64")):
+    for s, d in (("I16", "F16"), ("U16", "BF16"), ("F64", "I64"), ("U8", "BOOL"), ("F8_E5M2", "F16"), ("I64", "F64")):
         with pytest.raises(orc.OracleError) as e:
             orc.cast_array(np.zeros(8, np.uint8), s, d)
         assert e.value.kind == "CAST"
+
+
+# ---------------------------------------------------------------- binary64 <-> 16-bit types
+# One rounding from the 53-bit significand.  Independent references: numpy's direct float64 -> float16
+# conversion; round-half-even on exact rationals (Python's fractions); inputs built a hair beside every
+# tie of the target format, whose result is known by construction and which rounding twice (through
+# binary32) gets wrong; torch for the exact widenings.
+
+_FMT = {"F16": (10, 15), "BF16": (7, 127)}          # stored mantissa bits, exponent bias
+
+
+def _widen16(bits, fmt):
+    """Exact binary64 value of 16-bit patterns, by a library (numpy float16 / torch bfloat16)."""
+    bits = np.ascontiguousarray(bits, np.uint16)
+    if fmt == "F16":
+        return bits.view(np.float16).astype(np.float64)
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+
+
+def _near_tie_inputs(fmt):
+    """For every pair of neighbouring finite values a < b of the format (same sign): the midpoint
+    (exact in binary64) and the binary64 numbers just below and just above it, with the expected
+    16-bit result: lower neighbour, the even one, upper neighbour."""
+    mb, _ = _FMT[fmt]
+    top = 0x7C00 if fmt == "F16" else 0x7F80
+    lo = np.arange(0, top - 1, dtype=np.uint16)                 # 0 .. largest finite - 1
+    hi = lo + np.uint16(1)
+    a, b = _widen16(lo, fmt), _widen16(hi, fmt)
+    mid = (a + b) / 2                                           # exact: one more significant bit
+    below, above = np.nextafter(mid, -np.inf), np.nextafter(mid, np.inf)
+    even = np.where(lo & 1, hi, lo)
+    x = np.concatenate([below, mid, above])
+    want = np.concatenate([lo, even, hi]).astype(np.uint16)
+    # and the negative half
+    return np.concatenate([x, -x]), np.concatenate([want, want | np.uint16(0x8000)])
+
+
+@pytest.mark.parametrize("fmt", ["F16", "BF16"])
+def test_f64_to_16bit_near_every_tie(fmt):
+    x, want = _near_tie_inputs(fmt)
+    got = orc.cast_array(x.view(np.uint64), "F64", fmt)
+    assert np.array_equal(got, want)
+    # the same inputs rounded twice (binary64 -> binary32 -> 16 bit) differ: the pin can tell the two apart
+    twice = orc.cast_array(orc.cast_array(x.view(np.uint64), "F64", "F32"), "F32", fmt)
+    assert np.count_nonzero(twice != want) > 1000
+
+
+def _f64_samples_16(fmt):
+    """binary64 inputs over the 16-bit format's whole range: random patterns with the exponent drawn from
+    the format's span (a few binades beyond both ends), binary32 values widened (rounding twice is exact
+    there), plus the near-tie set."""
+    mb, bias = _FMT[fmt]
+    rng = np.random.default_rng(11)
+    e = rng.integers(1023 - bias - mb - 4, 1023 + bias + 4, 1_500_000, dtype=np.uint64)
+    m = rng.integers(0, 1 << 52, 1_500_000, dtype=np.uint64)
+    s = rng.integers(0, 2, 1_500_000, dtype=np.uint64) << np.uint64(63)
+    # low mantissa bits zeroed in a third of the samples: exact ties of the 16-bit format and values on its grid
+    keep = rng.integers(52 - mb - 2, 53, 1_500_000, dtype=np.uint64)
+    m2 = np.where(rng.random(1_500_000) < 0.33, (m >> keep) << keep, m)
+    return np.concatenate([s | (e << np.uint64(52)) | m2, rng.integers(0, 1 << 64, 500_000, dtype=np.uint64)])
+
+
+def test_f64_to_f16_vs_numpy():
+    d = np.concatenate([_f64_samples_16("F16"), _f64_samples()[::7]])
+    got = orc.cast_array(d, "F64", "F16")
+    with np.errstate(over="ignore", invalid="ignore", under="ignore"):
+        ref = d.view(np.float64).astype(np.float16).view(np.uint16)
+    ok = (d & np.uint64(0x7FFFFFFFFFFFFFFF)) <= np.uint64(0x7FF0000000000000)
+    assert np.array_equal(got[ok], ref[ok])
+
+
+@pytest.mark.parametrize("fmt", ["F16", "BF16"])
+def test_f64_to_16bit_vs_exact_rationals(fmt):
+    """Definition of round-to-nearest-even, carried out on exact rationals: the result is the multiple of
+    the local unit closest to x, ties to the even multiple (Python's round() on a Fraction does that)."""
+    from fractions import Fraction
+    mb, bias = _FMT[fmt]
+    emin = 1 - bias                                            # exponent of the smallest normal
+    d = _f64_samples_16(fmt)[::97]
+    d = d[(d & np.uint64(0x7FFFFFFFFFFFFFFF)) < np.uint64(0x7FF0000000000000)]
+    got = orc.cast_array(d, "F64", fmt)
+    max_finite = Fraction(2 - Fraction(1, 1 << mb)) * Fraction(2) ** bias
+    for bits, g in zip(d.tolist(), got.tolist()):
+        x = float(np.array([bits], np.uint64).view(np.float64)[0])
+        sign = 0x8000 if bits >> 63 else 0
+        ax = abs(Fraction(x))
+        if ax == 0:
+            assert g == sign
+            continue
+        e = max(ax.numerator.bit_length() - ax.denominator.bit_length(), emin - 1)
+        while Fraction(2) ** e > ax and e > emin:              # floor(log2 |x|), not below emin
+            e -= 1
+        while Fraction(2) ** (e + 1) <= ax:
+            e += 1
+        e = max(e, emin)
+        unit = Fraction(2) ** (e - mb)
+        q = round(ax / unit)                                   # half to even
+        val = q * unit
+        if val > max_finite:                                   # rounds past the largest finite value
+            want = sign | (0x7C00 if fmt == "F16" else 0x7F80)
+        else:
+            # encode val = q * 2^(e-mb): q < 2^mb is subnormal (e == emin), q == 2^(mb+1) carries into the next binade
+            if q == 1 << (mb + 1):
+                q, e = 1 << mb, e + 1
+            want = sign | (q if q < (1 << mb) else ((e + bias) << mb) | (q - (1 << mb)))
+        assert g == want, (hex(bits), hex(g), hex(want))
+
+
+@pytest.mark.parametrize("fmt", ["F16", "BF16"])
+def test_16bit_to_f64_exhaustive_and_back(fmt):
+    got = orc.cast_array(ALL16, fmt, "F64")
+    ref = _widen16(ALL16, fmt).view(np.uint64)
+    nan = _is_nan16(ALL16, *((0x7C00, 0x03FF) if fmt == "F16" else (0x7F80, 0x007F)))
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(orc.cast_array(got[~nan], "F64", fmt), ALL16[~nan])      # widening is exact
+    # widening in two exact steps or one gives the same bits, NaN included
+    assert np.array_equal(got, orc.cast_array(orc.cast_array(ALL16, fmt, "F32"), "F32", "F64"))
+
+
+def test_f64_16bit_constants_and_nan():
+    h = lambda v: int(orc.cast_array(np.array([v], np.uint64), "F64", "F16")[0])
+    b = lambda v: int(orc.cast_array(np.array([v], np.uint64), "F64", "BF16")[0])
+    assert h(0x3FF0000000000000) == 0x3C00 and b(0x3FF0000000000000) == 0x3F80        # 1.0
+    assert h(0xC004000000000000) == 0xC100 and b(0xC004000000000000) == 0xC020        # -2.5
+    assert h(0x3FF0020000000000) == 0x3C00            # 1 + 2^-11: tie -> even (down)
+    assert h(0x3FF0020000000001) == 0x3C01            # one binary64 ulp above the tie: up (via binary32: 0x3C00)
+    assert h(0x3FF0060000000000) == 0x3C02            # 1 + 3*2^-11: tie -> even (up)
+    assert b(0x3FF0100000000000) == 0x3F80            # 1 + 2^-8: tie -> even (down)
+    assert b(0x3FF0100000000001) == 0x3F81            # just above (via binary32: 0x3F80)
+    assert b(0x3FF0300000000000) == 0x3F82
+    assert h(0x40EFFC0000000000) == 0x7BFF            # 65504, largest finite
+    assert h(0x40EFFDFFFFFFFFFF) == 0x7BFF            # just below 65520
+    assert h(0x40EFFE0000000000) == 0x7C00            # 65520: tie -> even = infinity
+    assert h(0x3E70000000000000) == 0x0001            # 2^-24, smallest subnormal
+    assert h(0x3E60000000000000) == 0x0000            # 2^-25: tie between 0 and 2^-24 -> 0
+    assert h(0x3E60000000000001) == 0x0001
+    assert h(0x3E78000000000000) == 0x0002            # 1.5 * 2^-24: tie -> even
+    assert h(0x3F0FFE0000000000) == 0x0400            # (2^11 - 1) * 2^-25: tie -> smallest normal
+    assert b(0x47EFE00000000000) == 0x7F7F            # largest finite bfloat16
+    assert b(0x47EFF00000000000) == 0x7F80            # midpoint to 2^128: tie -> even = infinity
+    assert b(0x47EFEFFFFFFFFFFF) == 0x7F7F
+    assert b(0x37A0000000000000) == 0x0001            # 2^-133, smallest subnormal
+    assert b(0x3790000000000000) == 0x0000 and b(0x3790000000000001) == 0x0001
+    assert b(0x0000000000000001) == 0 and h(0x8000000000000001) == 0x8000
+    assert h(0x7FF0000000000000) == 0x7C00 and b(0xFFF0000000000000) == 0xFF80
+    rng = np.random.default_rng(12)
+    d = rng.integers(0, 1 << 64, 100000, dtype=np.uint64) | np.uint64(0x7FF0000000000000)
+    d = d[(d & np.uint64(0xFFFFFFFFFFFFF)) != 0]
+    n = orc.cast_array(d, "F64", "F16")
+    assert np.all((n & 0x7E00) == 0x7E00) and np.array_equal(n >> 15, (d >> np.uint64(63)).astype(np.uint16))
+    assert np.array_equal(n & 0x1FF, ((d >> np.uint64(42)) & np.uint64(0x1FF)).astype(np.uint16))
+    n = orc.cast_array(d, "F64", "BF16")
+    assert np.all((n & 0x7FC0) == 0x7FC0) and np.array_equal(n >> 15, (d >> np.uint64(63)).astype(np.uint16))
+    assert np.array_equal(n & 0x3F, ((d >> np.uint64(45)) & np.uint64(0x3F)).astype(np.uint16))
