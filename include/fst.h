@@ -294,7 +294,10 @@ int fst_launch(const fst_plan *p, size_t group, const void *src_dev, size_t src_
  * buffer in host memory and copied to the device from there.  Here the bounce buffer is a ring
  * of pinned slots filled by reader threads; hipMemcpyAsync on a copy stream drains it, and each
  * group is materialized on a compute stream as soon as its last byte has landed, so kernels
- * overlap the copies of later groups.
+ * overlap the copies of later groups.  Both streams belong to the stager and are not ordered with
+ * any stream of the caller: work the caller has queued on the raw, output, slot or workspace
+ * buffers must have finished before fst_stage_* is called (the calls themselves return only after
+ * everything they queued has finished).
  */
 
 /* Read callback: fill dst[0..len) with bytes [off, off+len) of file `file`; 0 on success. */

@@ -136,6 +136,38 @@ constexpr uint32_t XCD_RUN = 32;
 // that holds the span's first tile) plus a closing entry per launch (its last piece): the owner of
 // a tile lies between its span's entry and the next one; for large tensors the two coincide.
 constexpr uint32_t HINT_SPAN = 64;
+// The work-item count of one dispatch (workgroups x workgroup size) must fit 32 bits, so a launch
+// class with more tiles than MAX_LAUNCH_TILES goes out as several launches, each with the index of
+// its first tile as an argument.  The limit is a whole number of permutation spans, so that every
+// launch but the last of a class permutes whole spans (tile_of_workgroup).
+constexpr uint32_t MAX_LAUNCH_TILES =
+    uint32_t(((uint64_t(1) << 32) / VEC_BLOCK_THREADS - 1) / (XCD_COUNT * XCD_RUN) * (XCD_COUNT * XCD_RUN));
+struct LaunchPart { uint32_t tile_base, n_tiles; };
+inline std::vector<LaunchPart> split_launch(uint32_t n_tiles, uint32_t max_tiles = MAX_LAUNCH_TILES)
+{
+    std::vector<LaunchPart> parts;
+    for (uint32_t at = 0; at < n_tiles;) {
+        const uint32_t n = n_tiles - at < max_tiles ? n_tiles - at : max_tiles;
+        parts.push_back({at, n});
+        at += n;
+    }
+    return parts;
+}
+// Workgroup index -> tile index inside one launch of n_wg workgroups.  Workgroup i runs on XCD
+// i % 8; within every span of 8*XCD_RUN workgroups, XCD x gets the tiles x*XCD_RUN ..
+// x*XCD_RUN+XCD_RUN-1 of the span, in order.  A bijection of [0, n_wg).
+#ifdef __HIPCC__
+#define FST_HOST_DEVICE __host__ __device__
+#else
+#define FST_HOST_DEVICE
+#endif
+FST_HOST_DEVICE inline uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_wg)
+{
+    constexpr uint32_t SPAN = XCD_COUNT * XCD_RUN;
+    if (wg >= n_wg / SPAN * SPAN) return wg;             // the ragged last span keeps its order
+    const uint32_t r = wg % SPAN;
+    return wg - r + (r % XCD_COUNT) * XCD_RUN + r / XCD_COUNT;
+}
 // Vector pieces are cut so that chunk indices inside a piece fit 32 bits.
 constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;
 // Spliced pieces are cut so that element indices inside a piece stay below 2^31.

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <unordered_set>
 
@@ -359,7 +360,10 @@ static int parse_header_impl(const void *bytes, size_t nbytes, uint64_t file_siz
     if (nbytes < 8 + n)
         return fail(FST_E_TRUNCATED, "header needs %llu bytes, %zu given", (unsigned long long)(8 + n), nbytes);
 
-    fst_header *h = new (std::nothrow) fst_header;
+    // owned here until handed to the caller: an exception on the way (out of memory in a container)
+    // frees the half-built header
+    std::unique_ptr<fst_header> owner(new (std::nothrow) fst_header);
+    fst_header *h = owner.get();
     if (!h) return fail(FST_E_NOMEM, "out of memory");
     h->n_json = n;
     h->file_size = file_size;
@@ -371,7 +375,6 @@ static int parse_header_impl(const void *bytes, size_t nbytes, uint64_t file_siz
     auto bail = [&](int status, const char *what) {
         fail(status, "%s (near header byte %zu%s%s)", what, c.pos(text), key.empty() ? "" : ", key ",
              key.c_str());
-        delete h;
         return status;
     };
 
@@ -443,7 +446,7 @@ static int parse_header_impl(const void *bytes, size_t nbytes, uint64_t file_siz
         h->index[t.name] = i;
     }
     if (at != body_len) return bail(FST_E_OFFSETS, "tensors do not end where the file ends");
-    *out = h;
+    *out = owner.release();
     return FST_OK;
 }
 

@@ -444,22 +444,13 @@ __device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint
     if (CD == 32) gstore16(t + 16, o.hi);
 }
 
-// Workgroup index -> tile index.  Workgroup i runs on XCD i % 8; within every span of 8*XCD_RUN
-// workgroups, XCD x gets the tiles x*XCD_RUN .. x*XCD_RUN+XCD_RUN-1 of the span, in order.
-__device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_wg)
-{
-    constexpr uint32_t SPAN = XCD_COUNT * XCD_RUN;
-    if (wg >= n_wg / SPAN * SPAN) return wg;             // the ragged last span keeps its order
-    const uint32_t r = wg % SPAN;
-    return wg - r + (r % XCD_COUNT) * XCD_RUN + r / XCD_COUNT;
-}
-
 template <uint32_t CONV, bool BYTE>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs,
                                                                      const uint32_t *__restrict__ hints,
-                                                                     const uint8_t *__restrict__ raw)
+                                                                     const uint8_t *__restrict__ raw,
+                                                                     uint32_t tile_base)
 {
-    const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
+    const uint32_t b = tile_base + tile_of_workgroup(blockIdx.x, gridDim.x);
     const PieceRegs d = find_piece(descs, hints, b);
     const uint32_t t = b - d.tile0();                                   // tile inside the piece
     const uint32_t c0 = t * VEC_TILE_UNITS;                             // a piece has at most 2^31 chunks
@@ -504,12 +495,13 @@ __device__ __forceinline__ Chunk32 splice_chunk(const Chunk32 &a, const Chunk32 
 template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
-                                                                        const uint8_t *__restrict__ raw)
+                                                                        const uint8_t *__restrict__ raw,
+                                                                        uint32_t tile_base)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;                    // units per chunk
     constexpr uint32_t US = CS / CH;                                    // source bytes per unit
-    const uint32_t b = tile_of_workgroup(blockIdx.x, gridDim.x);
+    const uint32_t b = tile_base + tile_of_workgroup(blockIdx.x, gridDim.x);
     const PieceRegs d = find_piece(descs, hints, b);
     const uint32_t t = b - d.tile0();
     const uint32_t c0 = t * VEC_TILE_UNITS;
@@ -542,11 +534,12 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const De
 template <uint32_t CONV>
 __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
                                                                        const uint32_t *__restrict__ hints,
-                                                                       const uint8_t *__restrict__ raw)
+                                                                       const uint8_t *__restrict__ raw,
+                                                                       uint32_t tile_base)
 {
     constexpr uint32_t ES = ConvTraits<CONV>::SRC / ConvTraits<CONV>::UNITS;         // bytes per source element
     constexpr uint32_t ED = ConvTraits<CONV>::DST / ConvTraits<CONV>::UNITS;
-    const uint32_t b = blockIdx.x;
+    const uint32_t b = tile_base + blockIdx.x;
     const PieceRegs d = find_piece(descs, hints, b);
     const uint32_t t = b - d.tile0();
     const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
@@ -577,17 +570,20 @@ template <uint32_t CONV>
 int launch_conv(uint32_t variant, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles, const uint8_t *raw,
                 hipStream_t stream)
 {
-    const dim3 grid(n_tiles);
-    if (variant == 0)
-        hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
-    else if (variant == 1)
-        hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
-    else if (variant == 3)
-        hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw);
-    else
-        hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    for (const LaunchPart &part : split_launch(n_tiles)) {
+        const dim3 grid(part.n_tiles);
+        const uint32_t base = part.tile_base;
+        if (variant == 0)
+            hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+        else if (variant == 1)
+            hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+        else if (variant == 3)
+            hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+        else
+            hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    }
     return FST_OK;
 }
 

@@ -138,6 +138,7 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     const bool skip_read = (flags & FST_STAGE_NO_READ) != 0;
     if (!s || !p) return fail(FST_E_ARG, "fst_stage: NULL argument");
     if (!read && !skip_read) return fail(FST_E_ARG, "fst_stage: no read callback");
+    if (kernels && !out_ptrs && !p->outputs.empty()) return fail(FST_E_ARG, "fst_stage: out_ptrs is NULL");
     const size_t ng = p->groups.size();
     const double t_start = now_s();
 

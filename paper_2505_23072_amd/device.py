@@ -92,6 +92,9 @@ def load_files(paths: Sequence[str], requests: Optional[Dict[str, B.Request]] = 
     fds = [os.open(p, os.O_RDONLY) for p in paths]
     try:
         arr = (ctypes.c_int * len(fds))(*fds)
+        # the stager's streams are not ordered with torch's: the allocator may have handed out blocks that
+        # earlier work on the current stream still uses
+        torch.cuda.current_stream(dev).synchronize()
         st.stage_resident(plan, B.read_fds_fn(), ctypes.addressof(arr), raw.data_ptr(), raw_len, ptrs,
                           ws.data_ptr(), ws.numel())
     finally:

@@ -128,6 +128,7 @@ class SafeTensorsFileLoader:
         fds = [os.open(p, os.O_RDONLY) for p in self._files]
         try:
             arr = (ctypes.c_int * len(fds))(*fds)
+            torch.cuda.current_stream(self._device).synchronize()    # the stager's streams are its own
             self._stager.stage_resident(plan, B.read_fds_fn(), ctypes.addressof(arr), raw.data_ptr(), raw_len, [0] * len(names),
                                         0, 0, B.FST_STAGE_NO_KERNELS)
         finally:

@@ -1,5 +1,7 @@
 """Tensors longer than one kernel piece (a piece holds at most 2^31 chunks = 32 GiB of 16-byte chunks):
-the planner cuts them, and chunk indices stay below 2^31 inside every piece.  The bytes come from the
+the planner cuts them, and chunk indices stay below 2^31 inside every piece.  A launch class with more
+tiles than one dispatch can hold (4 194 048 tiles = 64 GiB - 4 MiB of 16-byte chunks) goes out as several
+dispatches.  The bytes come from the
 procedural source through the staging ring.  Every output byte is compared on the device with the raw
 buffer itself (a whole-tensor copy and a column slice have plain definitions as array slices), and
 windows around the cut, the start and the end are compared with the oracle on the host."""
@@ -37,8 +39,9 @@ def _stage(spec, names, reqs, rank=0, world=1):
     return model, plan, raw, bufs
 
 
-def test_one_row_of_33_gib_plus_a_ragged_tail():
-    n = 33 * GiB + 5
+def test_one_row_of_65_gib_plus_a_ragged_tail():
+    """Three pieces (cuts at 32 and 64 GiB) in one launch class that needs two dispatches."""
+    n = 65 * GiB + 5
     spec = ModelSpec("one-long-vector", 41, [FileSpec("a.safetensors", [
         TensorSpec("lead", "U8", (3,), fill="bytes"), TensorSpec("big", "U8", (n,), fill="bytes")], 9)])
     print(f"{spec.name}: {n} bytes", flush=True)
@@ -49,7 +52,9 @@ def test_one_row_of_33_gib_plus_a_ragged_tail():
     for at in range(0, n, 4 * GiB):                         # every byte, on the device
         m = min(4 * GiB, n - at)
         assert torch.equal(out[at:at + m], raw[begin + at:begin + at + m]), f"bytes [{at}, {at + m}) differ"
-    for at in (0, 32 * GiB - 4096, n - 8192):               # around the cut, against the oracle
+    first_of_second_dispatch = 4194048 * 16384
+    # around the piece cuts, around the first tile of the second dispatch, and the ragged end, against the oracle
+    for at in (0, 32 * GiB - 4096, first_of_second_dispatch - 4096, 64 * GiB - 4096, n - 8192):
         stored = model.read(0, begin + at, 8192)
         want, _ = orc.materialize(stored, "U8", (8192,))
         assert out[at:at + 8192].cpu().numpy().tobytes() == want.tobytes(), f"window at {at}"
