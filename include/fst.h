@@ -265,6 +265,21 @@ int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *
                          void *stream);
 
 /*
+ * fst_materialize (resident layout) for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The tables go into a
+ * workspace of FST_STATIC_WORKSPACE_BYTES that is built into the library (one per GPU, held until
+ * the process ends) instead of a caller-allocated one; the call allocates and frees no device
+ * memory.  FST_E_RANGE, before anything is enqueued, when the tables of `group` (or of all groups)
+ * may not fit: a piece takes 64 bytes and every MiB of output 4 more.  Every call on a GPU uses
+ * that GPU's one workspace and overwrites what the previous call left there: calls on one stream
+ * are ordered; calls that overlap on different streams of one GPU race, as do calls from several
+ * threads.  Everything else (arguments, checks, kernels, results) is fst_materialize's.
+ */
+#define FST_STATIC_WORKSPACE_BYTES (4u << 20)
+int fst_materialize_static(const void *raw_dev, size_t raw_len, const fst_plan *p, size_t group,
+                           void *const *out_ptrs, void *stream);
+
+/*
  * The two halves of fst_materialize, for callers that launch a group more than once or want the
  * launch apart from the table upload (timing the kernels alone; a ring of device slots that all
  * hold the same group layout).

@@ -106,6 +106,7 @@ _SIGNATURES = {
                                 c_void_p]),
     "fst_materialize_slot": (c_int, [c_void_p, c_size_t, c_void_p, c_size_t, POINTER(c_void_p), c_void_p,
                                      c_size_t, c_void_p]),
+    "fst_materialize_static": (c_int, [c_void_p, c_size_t, c_void_p, c_size_t, POINTER(c_void_p), c_void_p]),
     "fst_prepare": (c_int, [c_void_p, c_size_t, c_int32, c_size_t, POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
     "fst_launch": (c_int, [c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]),
     "fst_stager_create": (c_int, [POINTER(fst_stager_config), POINTER(c_void_p)]),
@@ -332,6 +333,16 @@ def fst_materialize_slot(slot_ptr: int, slot_len: int, plan: Plan, group: int, o
                          workspace_ptr: int, workspace_len: int, stream: int = 0) -> None:
     _check(lib().fst_materialize_slot(c_void_p(slot_ptr), slot_len, plan.handle, group, _ptr_array(out_ptrs),
                                       c_void_p(workspace_ptr), workspace_len, c_void_p(stream)))
+
+
+FST_STATIC_WORKSPACE_BYTES = 4 << 20
+
+
+def fst_materialize_static(raw_ptr: int, raw_len: int, plan: Plan, group: int, out_ptrs: Sequence[int],
+                           stream: int = 0) -> None:
+    """fst_materialize with the library's built-in workspace: no device allocation anywhere."""
+    _check(lib().fst_materialize_static(c_void_p(raw_ptr), raw_len, plan.handle, group, _ptr_array(out_ptrs),
+                                        c_void_p(stream)))
 
 
 FST_LAYOUT_RESIDENT, FST_LAYOUT_SLOT = 0, 1

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfst.so")
-SOURCES = ["header.cpp", "plan.cpp", "kernels.hip", "materialize.hip", "stage.hip"]
+SOURCES = ["header.cpp", "plan.cpp", "kernels.hip", "materialize.hip", "static_ws.hip", "stage.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

@@ -218,6 +218,8 @@ struct fst_plan {
     // source; re-cutting the groups drops them.
     mutable std::mutex image_mu;
     mutable std::map<size_t, fst::TableImage> images;
+    // the same for calls that upload into the library's built-in workspace (fst_materialize_static)
+    mutable std::map<size_t, fst::TableImage> builtin_images;
 };
 
 namespace fst {
@@ -229,6 +231,10 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
                 TableImage &image);
 // table_dev: where image.blob was copied.
 int launch_ranges(const TableImage &image, const void *table_dev, const void *src_dev, void *stream);
+// fst_materialize with the table kept in `images` (the plan's map for caller workspaces or the one
+// for the built-in workspace).
+int materialize_into(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
+                     void *ws, size_t ws_len, void *stream, bool slot, bool builtin);
 // Launch the kernels of one class.  descs_dev / hints_dev: the class's arrays on the device.
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
                          const void *raw_dev, void *stream);

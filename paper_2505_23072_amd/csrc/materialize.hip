@@ -140,11 +140,11 @@ int group_range(const fst_plan *p, size_t group, bool slot, size_t &g0, size_t &
 
 // Builds the group's table and enqueues its upload into the workspace.  Caller holds image_mu.
 int prepare_locked(const fst_plan *p, size_t group, bool slot, size_t src_len, void *const *out_ptrs, void *ws,
-                   size_t ws_len, void *stream)
+                   size_t ws_len, void *stream, bool builtin = false)
 {
     size_t g0, g1;
     if (int rc = group_range(p, group, slot, g0, g1)) return rc;
-    TableImage &image = p->images[group];
+    TableImage &image = (builtin ? p->builtin_images : p->images)[group];
     image.dev = nullptr;
     size_t n_pieces = 0;
     for (size_t g = g0; g < g1; ++g) n_pieces += p->groups[g].pieces.size();
@@ -167,10 +167,12 @@ int prepare_locked(const fst_plan *p, size_t group, bool slot, size_t src_len, v
 }
 
 // Enqueues the kernels of a prepared group.  Caller holds image_mu.
-int launch_locked(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream)
+int launch_locked(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream,
+                  bool builtin = false)
 {
-    auto it = p->images.find(group);
-    if (it == p->images.end() || !it->second.prepared)
+    const std::map<size_t, TableImage> &images = builtin ? p->builtin_images : p->images;
+    auto it = images.find(group);
+    if (it == images.end() || !it->second.prepared)
         return fail(FST_E_ARG, "group %zu has no uploaded table: call fst_prepare first", group);
     const TableImage &image = it->second;
     if (image.ranges.empty()) return FST_OK;
@@ -183,6 +185,16 @@ int launch_locked(const fst_plan *p, size_t group, const void *src_dev, size_t s
 }
 
 }  // namespace
+
+int materialize_into(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
+                     void *ws, size_t ws_len, void *stream, bool slot, bool builtin)
+{
+    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
+    std::lock_guard<std::mutex> lock(p->image_mu);
+    if (int rc = prepare_locked(p, group, slot, src_len, out_ptrs, ws, ws_len, stream, builtin)) return rc;
+    return launch_locked(p, group, src_dev, src_len, stream, builtin);
+}
+
 }  // namespace fst
 
 using namespace fst;
@@ -213,10 +225,7 @@ int launch_impl(const fst_plan *p, size_t group, const void *src_dev, size_t src
 int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
                      void *ws, size_t ws_len, void *stream, bool slot)
 {
-    if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
-    std::lock_guard<std::mutex> lock(p->image_mu);
-    if (int rc = prepare_locked(p, group, slot, src_len, out_ptrs, ws, ws_len, stream)) return rc;
-    return launch_locked(p, group, src_dev, src_len, stream);
+    return materialize_into(src_dev, src_len, p, group, out_ptrs, ws, ws_len, stream, slot, false);
 }
 
 }  // namespace

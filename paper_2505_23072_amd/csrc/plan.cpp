@@ -214,6 +214,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap)
     {
         std::lock_guard<std::mutex> lock(p->image_mu);
         p->images.clear();
+        p->builtin_images.clear();
     }
     p->descs.clear();
     p->groups.clear();

@@ -6,6 +6,7 @@ extern "C" {
 int fst_prepare(const fst_plan *, size_t, int32_t, size_t, void *const *, void *, size_t, void *) { return FST_E_HIP; }
 int fst_launch(const fst_plan *, size_t, const void *, size_t, void *) { return FST_E_HIP; }
 int fst_materialize(const void *, size_t, const fst_plan *, size_t, void *const *, void *, size_t, void *) { return FST_E_HIP; }
+int fst_materialize_static(const void *, size_t, const fst_plan *, size_t, void *const *, void *) { return FST_E_HIP; }
 int fst_materialize_slot(const void *, size_t, const fst_plan *, size_t, void *const *, void *, size_t, void *) { return FST_E_HIP; }
 int fst_stager_create(const fst_stager_config *, fst_stager **) { return FST_E_HIP; }
 void fst_stager_destroy(fst_stager *) {}
