@@ -46,7 +46,7 @@ typedef enum fst_status {
     FST_E_DUP_NAME = -8,       /* a key twice in one file, or one name in two files */
     FST_E_NOT_FOUND = -9,      /* requested name is in no file */
     FST_E_SHARD = -10,         /* bad shard dim / rank / world / blocks, or dim not divisible */
-    FST_E_CAST = -11,          /* conversion other than among {F32, F16, BF16} or F64 <-> F32 */
+    FST_E_CAST = -11,          /* conversion other than among {F64, F32, F16, BF16} */
     FST_E_ALIGN = -12,         /* a pointer or base offset misses its required alignment */
     FST_E_RANGE = -13,         /* too many dims, buffer too small, index out of range */
     FST_E_HIP = -14,           /* a HIP runtime call failed */
@@ -120,9 +120,9 @@ void fst_header_free(fst_header *h);
  *
  * A request asks for one named tensor as one rank sees it:
  *   dst_dtype  FST_KEEP, or a floating-point type other than the stored one: any pair among
- *              F32, F16 and BF16, and F64 <-> F32 (conversion in the same pass as the copy,
- *              Section III-B; one rounding, to nearest even).  Any other pair with differing
- *              types: FST_E_CAST.
+ *              F64, F32, F16 and BF16 (conversion in the same pass as the copy, Section III-B;
+ *              one rounding, to nearest even, also from F64 to a 16-bit type).  Any other pair
+ *              with differing types: FST_E_CAST.
  *   shard_dim  -1 = whole tensor; d >= 0 = the rank's equal share of dimension d (Section III-B).
  *              Column-wise split of an input projection = dim 0 of the stored [out, in] matrix,
  *              row-wise split of an output projection = dim 1 (Section II-A).
@@ -184,6 +184,11 @@ int fst_plan_output(const fst_plan *p, size_t i, fst_output_info *out);
  *   e.slot_offset % FST_RAW_ALIGN == e.lo % FST_RAW_ALIGN, so every source keeps the alignment it has
  *   in the file; the slot must hold slot_bytes.
  *
+ * Packed layout: the slot images of all groups side by side in one buffer of
+ *   fst_plan_packed_bytes: group g's image starts at fst_group_info.packed_offset (a multiple of
+ *   FST_RAW_ALIGN).  What the slot layout is to a checkpoint that streams through device memory,
+ *   the packed layout is to one whose staged bytes stay: only what is staged takes room.
+ *
  * fst_plan_set_groups stages, per group, everything from its first to its last needed byte as one
  * extent (whole files when every tensor is requested: Section III-A).  fst_plan_set_groups_sparse
  * additionally leaves out file ranges that no requested piece reads when they are longer than
@@ -191,10 +196,22 @@ int fst_plan_output(const fst_plan *p, size_t i, fst_output_info *out);
  * III-B warns that selecting each rank's ranges degrades into many small scattered reads: a large
  * min_gap_bytes (megabytes) keeps every extent large.  In the resident layout the skipped ranges
  * of the raw buffer are simply never written nor read.
+ *
+ * fst_plan_set_groups_compact goes one step further for strided shares (a partition along an inner
+ * dimension: one segment per row; the blocks of a fused matrix): when a row segment is at least
+ * min_segment_bytes long, the stager reads the segments one by one and puts them back to back into
+ * the slot image (a compacted extent), so that nothing of the other ranks' columns crosses the bus
+ * and the kernels find one contiguous run.  One read per segment is what Section III-B warns
+ * against for storage: use it when the source serves small reads well (the page cache, a
+ * generator) and keep min_segment_bytes at a few KiB, or pass UINT64_MAX to switch it off.
+ * Groups with compacted extents exist in the slot and packed layouts only (FST_E_ARG in the
+ * resident layout, whose raw buffer mirrors the files).
  */
 int fst_plan_set_groups(fst_plan *p, uint64_t max_group_bytes, size_t *n_groups);
 int fst_plan_set_groups_sparse(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes,
                                size_t *n_groups);
+int fst_plan_set_groups_compact(fst_plan *p, uint64_t max_group_bytes, uint64_t min_gap_bytes,
+                                uint64_t min_segment_bytes, size_t *n_groups);
 
 typedef struct fst_group_info {
     uint32_t file;
@@ -206,11 +223,21 @@ typedef struct fst_group_info {
     uint64_t staged_bytes;           /* sum of the extents' lengths */
     uint64_t read_bytes;             /* source bytes the kernels read for this group */
     uint64_t write_bytes;            /* output bytes they write */
+    uint64_t packed_offset;          /* packed layout: where the group's slot image starts */
 } fst_group_info;
 
+/*
+ * A plain extent (n_rows == 1) stages file bytes [lo, hi) verbatim; its image is hi - lo bytes.
+ * A compacted extent (n_rows > 1) stages n_rows segments of row_bytes, segment r being file bytes
+ * [lo + r*stride, lo + r*stride + row_bytes), and its image holds them back to back
+ * (n_rows*row_bytes bytes); hi is the end of the last segment.  Either image starts at slot_offset,
+ * with slot_offset % FST_RAW_ALIGN == lo % FST_RAW_ALIGN.  Plain extents of a group are ascending
+ * and disjoint; compacted ones may lie inside the file range of others.
+ */
 typedef struct fst_extent {
-    uint64_t lo, hi;                 /* file byte range that must be present */
+    uint64_t lo, hi;                 /* file byte range the extent spans */
     uint64_t slot_offset;            /* slot layout: where byte lo sits in the slot */
+    uint64_t row_bytes, n_rows, stride;
 } fst_extent;
 
 size_t fst_plan_group_count(const fst_plan *p);
@@ -236,6 +263,8 @@ int fst_plan_descriptor(const fst_plan *p, size_t i, fst_descriptor *out);
 /* Totals over all groups: bytes read from the raw buffer and bytes written to outputs. */
 uint64_t fst_plan_read_bytes(const fst_plan *p);
 uint64_t fst_plan_write_bytes(const fst_plan *p);
+/* Packed layout: bytes of one buffer that holds every group's slot image. */
+uint64_t fst_plan_packed_bytes(const fst_plan *p);
 
 /* Device workspace (bytes) that fst_materialize* needs for its tables, for any group or all. */
 size_t fst_plan_workspace_bytes(const fst_plan *p);
@@ -270,7 +299,7 @@ int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *
  * workspace of FST_STATIC_WORKSPACE_BYTES that is built into the library (one per GPU, held until
  * the process ends) instead of a caller-allocated one; the call allocates and frees no device
  * memory.  FST_E_RANGE, before anything is enqueued, when the tables of `group` (or of all groups)
- * may not fit: a piece takes 64 bytes and every MiB of output 4 more.  Every call on a GPU uses
+ * may not fit: a piece takes 64 bytes and every 256 KiB of output 4 more.  Every call on a GPU uses
  * that GPU's one workspace and overwrites what the previous call left there: calls on one stream
  * are ordered; calls that overlap on different streams of one GPU race, as do calls from several
  * threads.  Everything else (arguments, checks, kernels, results) is fst_materialize's.
@@ -284,8 +313,8 @@ int fst_materialize_static(const void *raw_dev, size_t raw_len, const fst_plan *
  * launch apart from the table upload (timing the kernels alone; a ring of device slots that all
  * hold the same group layout).
  *
- * fst_prepare builds the table of `group` (or FST_ALL_GROUPS, resident layout only) for the given
- * layout and output pointers, checks every source range against src_len exactly as
+ * fst_prepare builds the table of `group` (or FST_ALL_GROUPS, in the resident and packed layouts)
+ * for the given layout and output pointers, checks every source range against src_len exactly as
  * fst_materialize does, and enqueues the upload into dev_workspace on `stream`.  The workspace
  * then belongs to that group until it is prepared again or the groups are re-cut.
  *
@@ -299,6 +328,7 @@ int fst_materialize_static(const void *raw_dev, size_t raw_len, const fst_plan *
  */
 #define FST_LAYOUT_RESIDENT 0
 #define FST_LAYOUT_SLOT 1
+#define FST_LAYOUT_PACKED 2
 int fst_prepare(const fst_plan *p, size_t group, int32_t layout, size_t src_len, void *const *out_ptrs,
                 void *dev_workspace, size_t workspace_len, void *stream);
 int fst_launch(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream);
@@ -350,6 +380,18 @@ int fst_stage_resident(fst_stager *s, const fst_plan *p, fst_read_fn read, void 
                        void *raw_dev, size_t raw_len, void *const *out_ptrs,
                        void *dev_workspace, size_t workspace_len, uint32_t flags,
                        fst_stage_stats *stats);
+
+/*
+ * Packed load: stage every group's extents into its slot image inside one buffer of
+ * fst_plan_packed_bytes (packed_dev, FST_RAW_ALIGN-aligned; FST_E_RANGE if packed_len is less) and
+ * materialize group after group.  The buffer then holds exactly what was staged -- with sparse and
+ * compacted groups a fraction of the files -- and can be materialized again with
+ * fst_prepare/fst_launch in FST_LAYOUT_PACKED.  Blocks until all work has finished on the device.
+ */
+int fst_stage_packed(fst_stager *s, const fst_plan *p, fst_read_fn read, void *read_ctx,
+                     void *packed_dev, size_t packed_len, void *const *out_ptrs,
+                     void *dev_workspace, size_t workspace_len, uint32_t flags,
+                     fst_stage_stats *stats);
 
 /*
  * Streamed load for checkpoints larger than device memory: the raw buffer is a ring of

@@ -3,10 +3,10 @@
  *
  * A plain, slow, scalar reader of the safetensors container (paper Section II-A, Fig. 1) that
  * materializes one tensor at a time: locate its bytes, keep one rank's partition along one
- * dimension (Section II-A last paragraph, Section III-B "partitioning tensors at a dimension to be
- * the same shape"), convert the element type (Section III-B, "convert data types ... in the same
- * process") and write the result contiguously in row-major order (Section III-A: strides follow
- * from dtype and shape).  Everything is exact, so the oracle is the definition written out.
+ * dimension (Section II-A last paragraph; Section III-B: equal, same-shaped partitions), convert
+ * the element type (Section III-B: conversion in the pass that fixes the alignment) and write the
+ * result contiguously in row-major order (Section III-A: strides follow from dtype and shape).
+ * Everything is exact, so the oracle is the definition written out.
  *
  * Only tests, the smoke check and the benchmark's CPU-baseline leg may use this library.  It
  * shares no code, header, table or helper with the GPU path.
@@ -34,7 +34,7 @@ enum {
     ORC_DUPLICATE = 8,      /* the same key twice */
     ORC_NOT_FOUND = 9,
     ORC_SHARD = 10,         /* bad dim / rank / world / blocks, or dim not divisible */
-    ORC_CAST = 11,          /* conversion outside {F32, F16, BF16} and F64 <-> F32 */
+    ORC_CAST = 11,          /* conversion outside {F64, F32, F16, BF16} */
     ORC_RANGE = 12,         /* output buffer too small, too many dims */
     ORC_IO = 13,
     ORC_NOMEM = 14

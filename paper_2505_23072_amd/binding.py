@@ -45,11 +45,12 @@ class fst_output_info(Structure):
 class fst_group_info(Structure):
     _fields_ = [("file", c_uint32), ("n_descriptors", c_uint32), ("n_extents", c_uint32), ("reserved", c_uint32),
                 ("lo", c_uint64), ("hi", c_uint64), ("slot_bytes", c_uint64), ("staged_bytes", c_uint64),
-                ("read_bytes", c_uint64), ("write_bytes", c_uint64)]
+                ("read_bytes", c_uint64), ("write_bytes", c_uint64), ("packed_offset", c_uint64)]
 
 
 class fst_extent(Structure):
-    _fields_ = [("lo", c_uint64), ("hi", c_uint64), ("slot_offset", c_uint64)]
+    _fields_ = [("lo", c_uint64), ("hi", c_uint64), ("slot_offset", c_uint64), ("row_bytes", c_uint64),
+                ("n_rows", c_uint64), ("stride", c_uint64)]
 
 
 class fst_descriptor(Structure):
@@ -93,6 +94,8 @@ _SIGNATURES = {
     "fst_plan_output": (c_int, [c_void_p, c_size_t, POINTER(fst_output_info)]),
     "fst_plan_set_groups": (c_int, [c_void_p, c_uint64, POINTER(c_size_t)]),
     "fst_plan_set_groups_sparse": (c_int, [c_void_p, c_uint64, c_uint64, POINTER(c_size_t)]),
+    "fst_plan_set_groups_compact": (c_int, [c_void_p, c_uint64, c_uint64, c_uint64, POINTER(c_size_t)]),
+    "fst_plan_packed_bytes": (c_uint64, [c_void_p]),
     "fst_plan_group_extent": (c_int, [c_void_p, c_size_t, c_size_t, POINTER(fst_extent)]),
     "fst_plan_group_count": (c_size_t, [c_void_p]),
     "fst_plan_group": (c_int, [c_void_p, c_size_t, POINTER(fst_group_info)]),
@@ -114,6 +117,8 @@ _SIGNATURES = {
     "fst_read_fds": (c_int, [c_void_p, c_int32, c_uint64, c_void_p, c_uint64]),
     "fst_stage_resident": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, POINTER(c_void_p),
                                    c_void_p, c_size_t, c_uint32, POINTER(fst_stage_stats)]),
+    "fst_stage_packed": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, POINTER(c_void_p),
+                                 c_void_p, c_size_t, c_uint32, POINTER(fst_stage_stats)]),
     "fst_stage_streamed": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, POINTER(c_void_p), c_size_t, c_size_t,
                                    POINTER(c_void_p), c_void_p, c_size_t, c_uint32, POINTER(fst_stage_stats)]),
 }
@@ -263,14 +268,22 @@ class Plan:
         return dict(dtype=DTYPE_NAMES[oi.dtype], shape=tuple(oi.shape[d] for d in range(oi.ndim)),
                     nbytes=oi.nbytes, align=oi.align, file=oi.file)
 
-    def set_groups(self, max_group_bytes: int, min_gap_bytes: Optional[int] = None) -> int:
-        """min_gap_bytes given: do not stage unread file ranges longer than that."""
+    def set_groups(self, max_group_bytes: int, min_gap_bytes: Optional[int] = None,
+                   min_segment_bytes: Optional[int] = None) -> int:
+        """min_gap_bytes given: do not stage unread file ranges longer than that.  min_segment_bytes given:
+        stage the row segments of strided shares one by one, back to back, when they are at least that long."""
         n = c_size_t()
-        if min_gap_bytes is None:
+        if min_segment_bytes is not None:
+            gap = ctypes.c_uint64(-1).value if min_gap_bytes is None else min_gap_bytes
+            _check(lib().fst_plan_set_groups_compact(self._p, max_group_bytes, gap, min_segment_bytes, byref(n)))
+        elif min_gap_bytes is None:
             _check(lib().fst_plan_set_groups(self._p, max_group_bytes, byref(n)))
         else:
             _check(lib().fst_plan_set_groups_sparse(self._p, max_group_bytes, min_gap_bytes, byref(n)))
         return n.value
+
+    def packed_bytes(self) -> int:
+        return lib().fst_plan_packed_bytes(self._p)
 
     def group_count(self) -> int:
         return lib().fst_plan_group_count(self._p)
@@ -279,11 +292,13 @@ class Plan:
         gi = fst_group_info()
         _check(lib().fst_plan_group(self._p, g, byref(gi)))
         out = {k: getattr(gi, k) for k, _ in fst_group_info._fields_}
-        out["extents"] = []
+        out["extents"] = []           # (lo, hi, slot_offset)
+        out["extent_rows"] = []       # (row_bytes, n_rows, stride): n_rows > 1 = compacted
         for i in range(gi.n_extents):
             e = fst_extent()
             _check(lib().fst_plan_group_extent(self._p, g, i, byref(e)))
             out["extents"].append((e.lo, e.hi, e.slot_offset))
+            out["extent_rows"].append((e.row_bytes, e.n_rows, e.stride))
         return out
 
     def descriptor_count(self) -> int:
@@ -345,7 +360,7 @@ def fst_materialize_static(raw_ptr: int, raw_len: int, plan: Plan, group: int, o
                                         c_void_p(stream)))
 
 
-FST_LAYOUT_RESIDENT, FST_LAYOUT_SLOT = 0, 1
+FST_LAYOUT_RESIDENT, FST_LAYOUT_SLOT, FST_LAYOUT_PACKED = 0, 1, 2
 
 
 def fst_prepare(plan: Plan, group: int, layout: int, src_len: int, out_ptrs: Sequence[int], workspace_ptr: int,
@@ -373,6 +388,14 @@ class Stager:
         _check(lib().fst_stage_resident(self._s, plan.handle, c_void_p(read_fn), c_void_p(read_ctx),
                                         c_void_p(raw_ptr), raw_len, _ptr_array(out_ptrs), c_void_p(workspace_ptr),
                                         workspace_len, flags, byref(st)))
+        return {k: getattr(st, k) for k, _ in fst_stage_stats._fields_}
+
+    def stage_packed(self, plan: Plan, read_fn: int, read_ctx: int, packed_ptr: int, packed_len: int,
+                     out_ptrs: Sequence[int], workspace_ptr: int, workspace_len: int, flags: int = 0) -> dict:
+        st = fst_stage_stats()
+        _check(lib().fst_stage_packed(self._s, plan.handle, c_void_p(read_fn), c_void_p(read_ctx),
+                                      c_void_p(packed_ptr), packed_len, _ptr_array(out_ptrs), c_void_p(workspace_ptr),
+                                      workspace_len, flags, byref(st)))
         return {k: getattr(st, k) for k, _ in fst_stage_stats._fields_}
 
     def stage_streamed(self, plan: Plan, read_fn: int, read_ctx: int, slot_ptrs: Sequence[int], slot_bytes: int,

@@ -2,12 +2,13 @@
 // Section III-B: alignment fix and type conversion done in one pass on the GPU; one rank's
 // partition is taken in the same pass).  Pure data movement: HBM-bound, no matrix cores.
 //
-// Work is a table of pieces (DevDesc).  One workgroup of 1024 threads = 16 wavefronts takes one
-// tile of a piece; the piece is found through a hint table (one entry per HINT_SPAN tiles) with
-// scalar loads, since it only depends on the workgroup index.  In the vector and spliced paths a
-// lane moves one chunk: 16 source bytes when nothing is converted, 8 elements otherwise, always
-// written with full 16-byte stores to a 16-byte aligned destination.  Latency is covered by
-// occupancy (two workgroups = 32 wavefronts per CU), not by several loads per lane.
+// Work is a table of pieces (DevDesc).  A workgroup of 1024 threads = 16 wavefronts takes 16
+// consecutive tiles of its launch, one per wavefront (a tile is 64 chunks); the piece a tile
+// belongs to is found through a hint table (one entry per HINT_SPAN tiles) with scalar loads,
+// since it only depends on the workgroup and wavefront index.  In the vector, spliced and gather
+// paths a lane moves one chunk: 16 source bytes when nothing is converted, 8 elements otherwise (4
+// when binary64 is involved), written with full-width stores to an aligned destination.  Latency
+// is covered by occupancy (two workgroups = 32 wavefronts per CU), not by several loads per lane.
 //
 // The source may start at any byte.  Sources that are a multiple of 4 are read with 4-byte
 // aligned 16-byte loads.  Others read the enclosing aligned dwords (one more than the chunk
@@ -46,6 +47,15 @@ __device__ __forceinline__ void gstore16(void *p, u32x4 v)
 {
     __builtin_nontemporal_store(v, (FST_GLOBAL u32x4 *)(p));
 }
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
+__device__ __forceinline__ void gstore8(void *p, uint32_t x, uint32_t y)
+{
+    u32x2 v;
+    v.x = x;
+    v.y = y;
+    __builtin_nontemporal_store(v, (FST_GLOBAL u32x2 *)(p));
+}
 
 struct Chunk32 { u32x4 lo, hi; };                        // up to 32 source or result bytes
 
@@ -69,6 +79,27 @@ __device__ __forceinline__ u32x4 load16(const uint8_t *src)
     r.y = shift_bytes(v.z, v.y, sh);
     r.z = shift_bytes(v.w, v.z, sh);
     r.w = shift_bytes(e, v.w, sh);
+    return r;
+}
+
+// 8 bytes (in .x and .y) from any address (BYTE) or from a 4-byte aligned one.
+template <bool BYTE>
+__device__ __forceinline__ u32x4 load8(const uint8_t *src)
+{
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (!BYTE) {
+        const u32x2 v = __builtin_nontemporal_load((const FST_GLOBAL u32x2_a4 *)(src));
+        r.x = v.x;
+        r.y = v.y;
+        return r;
+    }
+    const uintptr_t a = reinterpret_cast<uintptr_t>(src);
+    const uint32_t sh = uint32_t(a) & 3u;
+    const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
+    const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
+    const uint32_t e = sh ? gload4(p + 8) : 0u;
+    r.x = shift_bytes(v.y, v.x, sh);
+    r.y = shift_bytes(e, v.y, sh);
     return r;
 }
 
@@ -184,6 +215,24 @@ __device__ __forceinline__ uint32_t double_to_float(uint64_t x)
     return sign | r;
 }
 
+// binary64 -> binary32 rounded to odd: the binary32 neighbour towards zero, with its lowest bit set
+// when the value is not exact.  A second rounding to nearest even into a format at least two bits
+// shorter (binary16, bfloat16) then gives what one rounding from binary64 gives: the odd last bit
+// keeps an inexact value off every tie and on the right side of it.  NaN goes by the NaN rule.
+__device__ __forceinline__ uint32_t double_to_float_odd(uint64_t x)
+{
+    if ((x & 0x7FFFFFFFFFFFFFFFull) > 0x7FF0000000000000ull) return double_to_float(x);
+    const double d = __longlong_as_double((long long)x);
+    const float f = float(d);                                   // to nearest even
+    uint32_t b = __float_as_uint(f);
+    const double back = double(f);
+    if (back != d) {                                            // inexact (an overflow to infinity included)
+        if (__builtin_fabs(back) > __builtin_fabs(d)) b -= 1u;  // one step towards zero
+        b |= 1u;
+    }
+    return b;
+}
+
 template <uint32_t CONV> struct ConvTraits;
 // SRC / DST: bytes of one chunk before and after; UNITS: units per chunk (bytes when copying).
 template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 16; };
@@ -195,6 +244,10 @@ template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DS
 template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
 template <> struct ConvTraits<CONV_D2F> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 4; };
 template <> struct ConvTraits<CONV_F2D> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 4; };
+template <> struct ConvTraits<CONV_D2H> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
+template <> struct ConvTraits<CONV_D2B> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
+template <> struct ConvTraits<CONV_H2D> { static constexpr uint32_t SRC = 8, DST = 32, UNITS = 4; };
+template <> struct ConvTraits<CONV_B2D> { static constexpr uint32_t SRC = 8, DST = 32, UNITS = 4; };
 
 template <uint32_t CONV>
 __device__ __forceinline__ uint32_t convert_bits(uint32_t v)
@@ -214,6 +267,10 @@ __device__ __forceinline__ uint64_t convert_element(uint64_t v)
 {
     if (CONV == CONV_D2F) return double_to_float(v);
     if (CONV == CONV_F2D) return float_to_double(uint32_t(v));
+    if (CONV == CONV_D2H) return float_to_half(double_to_float_odd(v));
+    if (CONV == CONV_D2B) return float_to_bfloat(double_to_float_odd(v));
+    if (CONV == CONV_H2D) return float_to_double(half_to_float(uint32_t(v)));
+    if (CONV == CONV_B2D) return float_to_double(bfloat_to_float(uint32_t(v)));
     return convert_bits<CONV>(uint32_t(v));
 }
 
@@ -270,7 +327,7 @@ __device__ __forceinline__ uint32_t narrow_to_half_pair(f32x2 f)
 template <uint32_t CONV>
 __device__ __forceinline__ bool chunk_has_inf_or_nan(const Chunk32 &in)
 {
-    if (CONV == CONV_D2F) {
+    if (CONV == CONV_D2F || CONV == CONV_D2H || CONV == CONV_D2B) {
         // the exponent of a binary64 element sits in its upper word
         constexpr uint32_t MASK = 0x7FF00000u, LOW = 0x00100000u;
         const uint32_t acc = ((in.lo.y & MASK) + LOW) | ((in.lo.w & MASK) + LOW) | ((in.hi.y & MASK) + LOW) |
@@ -278,8 +335,11 @@ __device__ __forceinline__ bool chunk_has_inf_or_nan(const Chunk32 &in)
         return (acc & 0x80000000u) != 0;
     }
     constexpr bool WIDE = CONV == CONV_F2H || CONV == CONV_F2B || CONV == CONV_F2D;
-    constexpr uint32_t MASK = WIDE ? 0x7F800000u : CONV == CONV_B2H ? 0x7F807F80u : 0x7C007C00u;
-    constexpr uint32_t LOW = WIDE ? 0x00800000u : CONV == CONV_B2H ? 0x00800080u : 0x04000400u;
+    constexpr bool BF = CONV == CONV_B2H || CONV == CONV_B2D;           // (bfloat16 -> binary32 never gets here)
+    constexpr uint32_t MASK = WIDE ? 0x7F800000u : BF ? 0x7F807F80u : 0x7C007C00u;
+    constexpr uint32_t LOW = WIDE ? 0x00800000u : BF ? 0x00800080u : 0x04000400u;
+    if (ConvTraits<CONV>::SRC == 8)                                      // four 16-bit elements in two words
+        return ((((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW)) & 0x80008000u) != 0;
     uint32_t acc = ((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW) | ((in.lo.z & MASK) + LOW) |
                    ((in.lo.w & MASK) + LOW);
     if (ConvTraits<CONV>::SRC == 32)
@@ -331,11 +391,30 @@ __device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
         const uint64_t d = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.w))));
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
         o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
+    } else if (CONV == CONV_D2H || CONV == CONV_D2B) {
+        const uint32_t a = double_to_float_odd(in.lo.x | (uint64_t(in.lo.y) << 32));
+        const uint32_t b = double_to_float_odd(in.lo.z | (uint64_t(in.lo.w) << 32));
+        const uint32_t c = double_to_float_odd(in.hi.x | (uint64_t(in.hi.y) << 32));
+        const uint32_t d = double_to_float_odd(in.hi.z | (uint64_t(in.hi.w) << 32));
+        if (CONV == CONV_D2H) {
+            o.lo.x = narrow_to_half_pair(float_pair(a, b));
+            o.lo.y = narrow_to_half_pair(float_pair(c, d));
+        } else {
+            o.lo.x = narrow_to_bfloat_pair(float_pair(a, b));
+            o.lo.y = narrow_to_bfloat_pair(float_pair(c, d));
+        }
+    } else if (CONV == CONV_H2D || CONV == CONV_B2D) {
+        const f32x2 p = CONV == CONV_H2D ? widen_half_pair(in.lo.x) : widen_bfloat_pair(in.lo.x);
+        const f32x2 q = CONV == CONV_H2D ? widen_half_pair(in.lo.y) : widen_bfloat_pair(in.lo.y);
+        const uint64_t a = uint64_t(__double_as_longlong(double(p.x))), b = uint64_t(__double_as_longlong(double(p.y)));
+        const uint64_t c = uint64_t(__double_as_longlong(double(q.x))), d = uint64_t(__double_as_longlong(double(q.y)));
+        o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
+        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     }
     return o;
 }
 
-// One chunk: 8 elements (or 16 raw bytes) in, converted out.
+// One chunk: 8 elements (4 with binary64, or 16 raw bytes) in, converted out.
 template <uint32_t CONV>
 __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
 {
@@ -369,6 +448,18 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
         const uint64_t c = float_to_double(in.lo.z), d = float_to_double(in.lo.w);
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
         o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
+    } else if (CONV == CONV_D2H || CONV == CONV_D2B) {
+        const uint32_t a = uint32_t(convert_element<CONV>(in.lo.x | (uint64_t(in.lo.y) << 32)));
+        const uint32_t b = uint32_t(convert_element<CONV>(in.lo.z | (uint64_t(in.lo.w) << 32)));
+        const uint32_t c = uint32_t(convert_element<CONV>(in.hi.x | (uint64_t(in.hi.y) << 32)));
+        const uint32_t d = uint32_t(convert_element<CONV>(in.hi.z | (uint64_t(in.hi.w) << 32)));
+        o.lo.x = a | (b << 16);
+        o.lo.y = c | (d << 16);
+    } else if (CONV == CONV_H2D || CONV == CONV_B2D) {
+        const uint64_t a = convert_element<CONV>(in.lo.x & 0xFFFFu), b = convert_element<CONV>(in.lo.x >> 16);
+        const uint64_t c = convert_element<CONV>(in.lo.y & 0xFFFFu), d = convert_element<CONV>(in.lo.y >> 16);
+        o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
+        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     } else {
         o.lo.x = convert_bits<CONV>(in.lo.x) | (convert_bits<CONV>(in.lo.y) << 16);
         o.lo.y = convert_bits<CONV>(in.lo.z) | (convert_bits<CONV>(in.lo.w) << 16);
@@ -393,11 +484,14 @@ struct PieceRegs {
     __device__ __forceinline__ uint32_t n_tiles() const { return w[10]; }
     __device__ __forceinline__ uint32_t div_m() const { return w[11]; }
     __device__ __forceinline__ uint32_t div_s() const { return w[12]; }
+    __device__ __forceinline__ uint32_t unit0() const { return w[13]; }
+    __device__ __forceinline__ uint32_t grain() const { return w[14]; }
 };
 static_assert(offsetof(DevDesc, src_off) == 0 && offsetof(DevDesc, src_stride) == 8 && offsetof(DevDesc, dst) == 16 &&
               offsetof(DevDesc, n_units) == 24 && offsetof(DevDesc, units_per_row) == 32 &&
               offsetof(DevDesc, tile0) == 36 && offsetof(DevDesc, n_tiles) == 40 && offsetof(DevDesc, div_m) == 44 &&
-              offsetof(DevDesc, div_s) == 48, "PieceRegs reads DevDesc by dword position");
+              offsetof(DevDesc, div_s) == 48 && offsetof(DevDesc, unit0) == 52 && offsetof(DevDesc, grain) == 56,
+              "PieceRegs reads DevDesc by dword position");
 
 // The piece that owns tile `b`.  hints[k] names the piece that holds tile k*HINT_SPAN (the last
 // piece for the entry past the end), so the owner lies between hints[b/HINT_SPAN] and the next
@@ -422,6 +516,49 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t m, uint32_t s)
     return __umulhi(n << 1, m) >> s;
 }
 
+// What a wavefront works on: its tile's piece, the tile's first chunk inside the piece and the
+// number of chunks the tile holds (64 but for a piece's last tile).  Workgroup position p of the
+// launch (see tile_of_workgroup) takes tiles p*WG_TILES .. p*WG_TILES+15, one per wavefront; all
+// of it depends on the workgroup and wavefront index alone, so it lives in scalar registers.
+struct WaveTile {
+    PieceRegs d;
+    uint32_t c0, n;
+};
+__device__ __forceinline__ bool wave_tile(const DevDesc *__restrict__ descs, const uint32_t *__restrict__ hints,
+                                          uint32_t wg_base, uint32_t n_tiles, WaveTile &wt)
+{
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const uint32_t b = (wg_base + tile_of_workgroup(blockIdx.x, gridDim.x)) * WG_TILES + wave;
+    if (b >= n_tiles) return false;                                     // the launch's last workgroup may be short
+    wt.d = find_piece(descs, hints, b);
+    const uint32_t t = b - wt.d.tile0();                                // tile inside the piece
+    wt.c0 = t * VEC_TILE_UNITS;                                         // a piece has at most 2^31 chunks
+    // only a piece's last tile can be short; decided on 32-bit tile counts
+    wt.n = (t + 1 == wt.d.n_tiles()) ? uint32_t(wt.d.n_units()) - wt.c0 : VEC_TILE_UNITS;
+    return true;
+}
+
+template <uint32_t CS, bool BYTE>
+__device__ __forceinline__ Chunk32 load_chunk(const uint8_t *s)
+{
+    Chunk32 v;
+    if (CS == 8) v.lo = load8<BYTE>(s);
+    else if (CS == 16) v.lo = load16<BYTE>(s);
+    else v = load32<BYTE>(s);
+    return v;
+}
+
+template <uint32_t CD>
+__device__ __forceinline__ void store_chunk(uint8_t *t, const Chunk32 &o)
+{
+    if (CD == 8) {
+        gstore8(t, o.lo.x, o.lo.y);
+    } else {
+        gstore16(t, o.lo);
+        if (CD == 32) gstore16(t + 16, o.hi);
+    }
+}
+
 // One chunk per lane: chunk c of the piece (c < n_units) is read at its row/column offset from
 // `src` and written at dst + c*CD.
 template <uint32_t CONV, bool BYTE>
@@ -436,28 +573,21 @@ __device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint
         const uint32_t r = fast_div(c, d.div_m(), d.div_s());
         s = src + uint64_t(r) * d.src_stride() + uint64_t(c - r * upr) * CS;
     }
-    Chunk32 v;
-    if (CS == 16) v.lo = load16<BYTE>(s); else v = load32<BYTE>(s);
-    const Chunk32 o = convert_chunk<CONV>(v);
-    uint8_t *t = dst + uint64_t(c) * CD;
-    gstore16(t, o.lo);
-    if (CD == 32) gstore16(t + 16, o.hi);
+    const Chunk32 o = convert_chunk<CONV>(load_chunk<CS, BYTE>(s));
+    store_chunk<CD>(dst + uint64_t(c) * CD, o);
 }
 
 template <uint32_t CONV, bool BYTE>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs,
                                                                      const uint32_t *__restrict__ hints,
                                                                      const uint8_t *__restrict__ raw,
-                                                                     uint32_t tile_base)
+                                                                     uint32_t wg_base, uint32_t n_tiles)
 {
-    const uint32_t b = tile_base + tile_of_workgroup(blockIdx.x, gridDim.x);
-    const PieceRegs d = find_piece(descs, hints, b);
-    const uint32_t t = b - d.tile0();                                   // tile inside the piece
-    const uint32_t c0 = t * VEC_TILE_UNITS;                             // a piece has at most 2^31 chunks
-    // only a piece's last tile can be short; decided on 32-bit tile counts
-    const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units()) - c0 : VEC_TILE_UNITS;
-    if (threadIdx.x < n)
-        vec_chunk<CONV, BYTE>(raw + d.src_off(), reinterpret_cast<uint8_t *>(d.dst()), c0 + threadIdx.x, d);
+    WaveTile wt;
+    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    const uint32_t lane = threadIdx.x % WAVE;
+    if (lane < wt.n)
+        vec_chunk<CONV, BYTE>(raw + wt.d.src_off(), reinterpret_cast<uint8_t *>(wt.d.dst()), wt.c0 + lane, wt.d);
 }
 
 // Bytes [0, kb) of `a` followed by bytes [kb, ...) of `b`, word by word (kb in 1 .. size-1).
@@ -486,78 +616,172 @@ __device__ __forceinline__ Chunk32 splice_chunk(const Chunk32 &a, const Chunk32 
 }
 
 // Spliced path: rows that are not a whole number of chunks (a dim-1 share whose row segment is,
-// say, 2050 bytes).  The output is one contiguous stream; a lane owns one 16-byte aligned chunk of
-// it, i.e. CH consecutive units (bytes when copying, elements when converting).  Most chunks lie
-// inside one row and are read like a byte-aligned vector chunk.  A chunk that straddles a row end
-// takes its first k units from the end of row r and the rest from the start of row r+1: the second
-// read starts k units *before* row r+1 (inside row r's stride, since a row has at least CH units),
-// so that both reads hold their units at the chunk's own positions and a byte mask splices them.
+// say, 2050 bytes).  The output is one contiguous stream; a lane owns one aligned chunk of it,
+// i.e. CH consecutive units (bytes when copying, elements when converting); the piece's first unit
+// is unit unit0 of its first row (a piece starts on a store boundary of the output, which need not
+// be the start of a row).  Most chunks lie inside one row and are read like a byte-aligned vector
+// chunk.  A chunk that straddles a row end takes its first k units from the end of row r and the
+// rest from the start of row r+1: the second read starts k units *before* row r+1 (inside row r's
+// stride, since a row has at least CH units), so that both reads hold their units at the chunk's
+// own positions and a byte mask splices them.
 template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
                                                                         const uint8_t *__restrict__ raw,
-                                                                        uint32_t tile_base)
+                                                                        uint32_t wg_base, uint32_t n_tiles)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;                    // units per chunk
     constexpr uint32_t US = CS / CH;                                    // source bytes per unit
-    const uint32_t b = tile_base + tile_of_workgroup(blockIdx.x, gridDim.x);
-    const PieceRegs d = find_piece(descs, hints, b);
-    const uint32_t t = b - d.tile0();
-    const uint32_t c0 = t * VEC_TILE_UNITS;
-    const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units()) - c0 : VEC_TILE_UNITS;
-    if (threadIdx.x >= n) return;
-    const uint32_t c = c0 + threadIdx.x;
-    const uint32_t u0 = c * CH;                                         // the piece has fewer than 2^31 units
+    WaveTile wt;
+    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    const PieceRegs &d = wt.d;
+    const uint32_t lane = threadIdx.x % WAVE;
+    if (lane >= wt.n) return;
+    const uint32_t c = wt.c0 + lane;
+    const uint32_t u0 = d.unit0() + c * CH;                             // the piece ends below unit 2^31
     const uint32_t upr = d.units_per_row();
     const uint32_t r = fast_div(u0, d.div_m(), d.div_s());
     const uint32_t col = u0 - r * upr;
     const uint8_t *row = raw + d.src_off() + uint64_t(r) * d.src_stride();
-    Chunk32 v;
-    if (CS == 16) v.lo = load16<true>(row + uint64_t(col) * US); else v = load32<true>(row + uint64_t(col) * US);
+    Chunk32 v = load_chunk<CS, true>(row + uint64_t(col) * US);
     const uint32_t k = upr - col;                                       // units left in row r
     if (k < CH) {
         const uint8_t *next = row + d.src_stride() - k * US;
-        Chunk32 w;
-        if (CS == 16) w.lo = load16<true>(next); else w = load32<true>(next);
+        const Chunk32 w = load_chunk<CS, true>(next);
         v = splice_chunk<CS>(v, w, k * US);
     }
     const Chunk32 o = convert_chunk<CONV>(v);
-    uint8_t *out = reinterpret_cast<uint8_t *>(d.dst()) + uint64_t(c) * CD;
-    gstore16(out, o.lo);
-    if (CD == 32) gstore16(out + 16, o.hi);
+    store_chunk<CD>(reinterpret_cast<uint8_t *>(d.dst()) + uint64_t(c) * CD, o);
 }
 
-// Element path: tails shorter than a chunk, rows shorter than a chunk, and pieces whose first
-// output byte is not 16-byte aligned.  One element (one byte when nothing is converted) per thread
-// and step; sources are read bytewise; indices are 64-bit.
+// One unit of G bytes (1, 2, 4 or 8) from an address that is a multiple of G.
+template <uint32_t G>
+__device__ __forceinline__ uint64_t load_unit(const uint8_t *p)
+{
+    if (G == 1) return *(const FST_GLOBAL uint8_t *)(p);
+    if (G == 2) return *(const FST_GLOBAL uint16_t *)(p);
+    if (G == 4) return *(const FST_GLOBAL uint32_t *)(p);
+    return *(const FST_GLOBAL uint64_t *)(p);
+}
+// One element of ES bytes from any address, byte by byte.
+template <uint32_t ES>
+__device__ __forceinline__ uint64_t load_bytes(const uint8_t *p)
+{
+    uint64_t v = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < ES; ++k) v |= uint64_t(*(const FST_GLOBAL uint8_t *)(p + k)) << (8 * k);
+    return v;
+}
+// OR v into 32-bit word `word` of a chunk seen as eight words.
+__device__ __forceinline__ void chunk_or(Chunk32 &c, uint32_t word, uint32_t v)
+{
+    switch (word) {                                     // `word` is a compile-time constant after unrolling
+    case 0: c.lo.x |= v; break;
+    case 1: c.lo.y |= v; break;
+    case 2: c.lo.z |= v; break;
+    case 3: c.lo.w |= v; break;
+    case 4: c.hi.x |= v; break;
+    case 5: c.hi.y |= v; break;
+    case 6: c.hi.z |= v; break;
+    default: c.hi.w |= v; break;
+    }
+}
+
+// G consecutive source bytes of one row, starting at byte u of the piece's byte stream (copying).
+template <uint32_t G>
+__device__ __forceinline__ uint32_t gather_bytes(const uint8_t *base, const PieceRegs &d, uint32_t u)
+{
+    const uint32_t r = fast_div(u, d.div_m(), d.div_s());
+    return uint32_t(load_unit<G>(base + uint64_t(r) * d.src_stride() + (u - r * d.units_per_row())));
+}
+
+// Gather path: rows shorter than one chunk (a partition along the last dimension of a tensor whose
+// rows are a few elements long).  As in the spliced path a lane owns one aligned chunk of the
+// output stream, but its units come from several rows, so it fetches them one by one: with loads
+// of `grain` bytes when the geometry keeps every source address a multiple of it (1, 2, 4 or 8
+// bytes; never more than one unit when converting), byte by byte otherwise.  The stores are
+// full-width.  Neighbouring lanes read neighbouring rows, so every cache line is still fetched
+// once; what bounds this path is that a line is fetched whole for the few bytes kept of it.
+template <uint32_t CONV>
+__global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_gather(const DevDesc *__restrict__ descs,
+                                                                        const uint32_t *__restrict__ hints,
+                                                                        const uint8_t *__restrict__ raw,
+                                                                        uint32_t wg_base, uint32_t n_tiles)
+{
+    constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
+    constexpr uint32_t CH = ConvTraits<CONV>::UNITS;
+    constexpr uint32_t US = CS / CH;
+    WaveTile wt;
+    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    const PieceRegs &d = wt.d;
+    const uint32_t lane = threadIdx.x % WAVE;
+    if (lane >= wt.n) return;
+    const uint32_t c = wt.c0 + lane;
+    const uint32_t u0 = d.unit0() + c * CH;
+    const uint8_t *base = raw + d.src_off();
+    const uint32_t grain = d.grain();
+    Chunk32 v;
+    v.lo = u32x4{0u, 0u, 0u, 0u};
+    v.hi = u32x4{0u, 0u, 0u, 0u};
+    if (CONV == CONV_COPY) {
+        // 16 bytes; rows, strides and the first address are multiples of `grain`, so `grain`
+        // consecutive bytes never leave their row
+        if (grain >= 4) {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) chunk_or(v, j, gather_bytes<4>(base, d, u0 + 4 * j));
+        } else if (grain == 2) {
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j) chunk_or(v, j / 2, gather_bytes<2>(base, d, u0 + 2 * j) << (16 * (j % 2)));
+        } else {
+#pragma unroll
+            for (uint32_t j = 0; j < 16; ++j) chunk_or(v, j / 4, gather_bytes<1>(base, d, u0 + j) << (8 * (j % 4)));
+        }
+    } else {
+        const bool aligned = grain >= US;
+#pragma unroll
+        for (uint32_t j = 0; j < CH; ++j) {
+            const uint32_t u = u0 + j;
+            const uint32_t r = fast_div(u, d.div_m(), d.div_s());
+            const uint8_t *p = base + uint64_t(r) * d.src_stride() + uint64_t(u - r * d.units_per_row()) * US;
+            const uint64_t e = aligned ? load_unit<US>(p) : load_bytes<US>(p);
+            if (US == 2) chunk_or(v, j / 2, uint32_t(e) << (16 * (j % 2)));
+            else if (US == 4) chunk_or(v, j, uint32_t(e));
+            else { chunk_or(v, 2 * j, uint32_t(e)); chunk_or(v, 2 * j + 1, uint32_t(e >> 32)); }
+        }
+    }
+    const Chunk32 o = convert_chunk<CONV>(v);
+    store_chunk<CD>(reinterpret_cast<uint8_t *>(d.dst()) + uint64_t(c) * CD, o);
+}
+
+// Element path: the few units in front of a piece's first store boundary and behind its last whole
+// chunk, and rows too long for the 32-bit unit indices of the other paths.  One element (one byte
+// when nothing is converted) per thread and step; sources are read bytewise; indices are 64-bit.
 template <uint32_t CONV>
 __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
                                                                        const uint32_t *__restrict__ hints,
                                                                        const uint8_t *__restrict__ raw,
-                                                                       uint32_t tile_base)
+                                                                       uint32_t wg_base, uint32_t n_tiles)
 {
     constexpr uint32_t ES = ConvTraits<CONV>::SRC / ConvTraits<CONV>::UNITS;         // bytes per source element
     constexpr uint32_t ED = ConvTraits<CONV>::DST / ConvTraits<CONV>::UNITS;
-    const uint32_t b = tile_base + blockIdx.x;
+    const uint32_t b = wg_base + blockIdx.x;                                         // one tile per workgroup
     const PieceRegs d = find_piece(descs, hints, b);
     const uint32_t t = b - d.tile0();
     const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
     const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units() - e0) : ELEM_TILE_UNITS;
     const uint32_t upr = d.units_per_row();
     const uint64_t stride = d.src_stride();
-    const uint64_t row0 = e0 / upr;
-    const uint32_t col0 = uint32_t(e0 - row0 * upr);
+    const uint64_t g0 = uint64_t(d.unit0()) + e0;                                    // counted from the start of the piece's first row
+    const uint64_t row0 = g0 / upr;
+    const uint32_t col0 = uint32_t(g0 - row0 * upr);
     const uint8_t *src = raw + d.src_off() + row0 * stride;
     uint8_t *dst = reinterpret_cast<uint8_t *>(d.dst()) + e0 * ED;
     for (uint32_t i = threadIdx.x; i < n; i += ELEM_BLOCK_THREADS) {
         const uint64_t cc = uint64_t(col0) + i;
         const uint64_t r = cc / upr;
         const uint8_t *s = src + r * stride + (cc - r * upr) * ES;
-        uint64_t v = 0;
-#pragma unroll
-        for (uint32_t k = 0; k < ES; ++k) v |= uint64_t(*(const FST_GLOBAL uint8_t *)(s + k)) << (8 * k);
-        v = convert_element<CONV>(v);
+        const uint64_t v = convert_element<CONV>(load_bytes<ES>(s));
         uint8_t *o = dst + uint64_t(i) * ED;
         if (ED == 1) *(FST_GLOBAL uint8_t *)(o) = uint8_t(v);
         else if (ED == 2) *(FST_GLOBAL uint16_t *)(o) = uint16_t(v);
@@ -567,20 +791,27 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
 }
 
 template <uint32_t CONV>
-int launch_conv(uint32_t variant, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles, const uint8_t *raw,
-                hipStream_t stream)
+int launch_conv(uint32_t path, bool byte_aligned, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles,
+                const uint8_t *raw, hipStream_t stream)
 {
-    for (const LaunchPart &part : split_launch(n_tiles)) {
-        const dim3 grid(part.n_tiles);
-        const uint32_t base = part.tile_base;
-        if (variant == 0)
-            hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
-        else if (variant == 1)
-            hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
-        else if (variant == 3)
-            hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+    for (const LaunchPart &part : split_launch(workgroups_of(path, n_tiles))) {
+        const dim3 grid(part.n_wg);
+        const uint32_t base = part.wg_base;
+        if (path == PATH_VEC && !byte_aligned)
+            hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
+                               base, n_tiles);
+        else if (path == PATH_VEC)
+            hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
+                               base, n_tiles);
+        else if (path == PATH_SPLICE)
+            hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
+                               base, n_tiles);
+        else if (path == PATH_GATHER)
+            hipLaunchKernelGGL((materialize_gather<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
+                               base, n_tiles);
         else
-            hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw, base);
+            hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw,
+                               base, n_tiles);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     }
@@ -593,22 +824,25 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
                          const void *raw_dev, void *stream)
 {
     if (n_tiles == 0) return FST_OK;
-    uint32_t conv, variant;
-    if (cls < CONV_COUNT * 2) { conv = cls / 2; variant = cls % 2; }
-    else if (cls < CONV_COUNT * 3) { conv = cls - CONV_COUNT * 2; variant = 2; }
-    else { conv = cls - CONV_COUNT * 3; variant = 3; }
+    if (cls >= N_CLASSES) return fail(FST_E_ARG, "unknown launch class %u", cls);
+    const uint32_t path = class_path(cls), conv = class_conv(cls);
+    const bool byte_aligned = path == PATH_VEC && cls % 2 == 1;
     const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (conv) {
-    case CONV_COPY: return launch_conv<CONV_COPY>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_H2B: return launch_conv<CONV_H2B>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_B2H: return launch_conv<CONV_B2H>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_H2F: return launch_conv<CONV_H2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_B2F: return launch_conv<CONV_B2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2H: return launch_conv<CONV_F2H>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2B: return launch_conv<CONV_F2B>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_D2F: return launch_conv<CONV_D2F>(variant, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2D: return launch_conv<CONV_F2D>(variant, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_COPY: return launch_conv<CONV_COPY>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_H2B: return launch_conv<CONV_H2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_B2H: return launch_conv<CONV_B2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_H2F: return launch_conv<CONV_H2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_B2F: return launch_conv<CONV_B2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2H: return launch_conv<CONV_F2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2B: return launch_conv<CONV_F2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_D2F: return launch_conv<CONV_D2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_F2D: return launch_conv<CONV_F2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_D2H: return launch_conv<CONV_D2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_D2B: return launch_conv<CONV_D2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_H2D: return launch_conv<CONV_H2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_B2D: return launch_conv<CONV_B2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
     default: return fail(FST_E_ARG, "unknown launch class %u", cls);
     }
 }

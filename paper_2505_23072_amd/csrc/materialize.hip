@@ -33,23 +33,25 @@ void division_magic(uint32_t d, uint32_t &m, uint32_t &s)
 }  // namespace
 
 // Builds the device image for groups [g0, g1) as ONE launch set (pieces of all those groups
-// merged per class).  slot = true: sources are addressed for the slot layout of group g0 (g1 must
-// be g0+1): a piece's bytes are found through the extent that holds them.
-int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, bool slot,
+// merged per class).  In the slot layout (group g0 alone) and in the packed layout a piece's bytes
+// are found through the extent that holds them.
+int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, size_t src_len, int layout,
                 TableImage &image)
 {
     std::vector<DevDesc> &descs = image.descs;
     std::vector<LaunchRange> &ranges = image.ranges;
-    std::vector<const Piece *> order;
+    struct Ref { const Piece *pc; const Group *gr; };
+    std::vector<Ref> order;
     for (size_t g = g0; g < g1; ++g)
-        for (const Piece &pc : p->groups[g].pieces) order.push_back(&pc);
+        for (const Piece &pc : p->groups[g].pieces) order.push_back({&pc, &p->groups[g]});
     std::stable_sort(order.begin(), order.end(),
-                     [](const Piece *a, const Piece *b) { return launch_class(*a) < launch_class(*b); });
+                     [](const Ref &a, const Ref &b) { return launch_class(*a.pc) < launch_class(*b.pc); });
     descs.clear();
     ranges.clear();
     image.hints.clear();
     descs.reserve(order.size());
-    for (const Piece *pc : order) {
+    for (const Ref &ref : order) {
+        const Piece *pc = ref.pc;
         const Output &o = p->outputs[pc->output];
         const uintptr_t out = reinterpret_cast<uintptr_t>(out_ptrs[pc->output]);
         if (out == 0) return fail(FST_E_ARG, "out_ptrs[%u] is NULL but the output has %llu bytes", pc->output,
@@ -57,17 +59,19 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         if (out % FST_OUTPUT_ALIGN)
             return fail(FST_E_ALIGN, "out_ptrs[%u] is not %d-byte aligned", pc->output, FST_OUTPUT_ALIGN);
         uint64_t src_off;
-        if (slot) {
-            // the extent with the largest lo <= the piece's first byte
-            const std::vector<Extent> &ex = p->groups[g0].extents;
-            auto it = std::upper_bound(ex.begin(), ex.end(), pc->src_file_off,
-                                       [](uint64_t v, const Extent &e) { return v < e.lo; });
-            if (it == ex.begin() || pc->src_file_off + pc->src_span > (it - 1)->hi)
-                return fail(FST_E_RANGE, "output %u: source bytes are not inside one staged extent", pc->output);
-            --it;
-            src_off = it->slot_off + (pc->src_file_off - it->lo);
-        } else {
+        if (layout == FST_LAYOUT_RESIDENT) {
+            if (pc->compact)
+                return fail(FST_E_ARG, "the plan's groups stage compacted rows: use the slot or the packed layout");
             src_off = p->raw_base[o.info.file] + pc->src_file_off;
+        } else {
+            if (pc->extent >= ref.gr->extents.size()) return fail(FST_E_ARG, "output %u: no staged extent", pc->output);
+            const Extent &ex = ref.gr->extents[pc->extent];
+            // a piece over a compacted extent is laid out over the extent's image; others sit at their file offset
+            const uint64_t inside = pc->compact ? pc->src_file_off : pc->src_file_off - ex.lo;
+            if ((!pc->compact && (pc->src_file_off < ex.lo || pc->src_file_off + pc->src_span > ex.hi)) ||
+                (pc->compact && inside + pc->src_span > ex.image_bytes()))
+                return fail(FST_E_RANGE, "output %u: source bytes are not inside their staged extent", pc->output);
+            src_off = (layout == FST_LAYOUT_PACKED ? ref.gr->packed_off : 0) + ex.slot_off + inside;
         }
         // the kernels read whole dwords around unaligned bytes: round the end up to 4
         const uint64_t end = (src_off + pc->src_span + 3) & ~uint64_t(3);
@@ -83,6 +87,8 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         d.dst = uint64_t(out) + pc->dst_off;
         d.n_units = pc->n_units;
         d.units_per_row = pc->units_per_row;
+        d.unit0 = pc->unit0;
+        d.grain = pc->grain;
         d.tile0 = r.tiles;
         d.n_tiles = tiles_of(*pc);
         if (pc->path != PATH_ELEM && pc->units_per_row) division_magic(pc->units_per_row, d.div_m, d.div_s);
@@ -124,10 +130,10 @@ int launch_ranges(const TableImage &image, const void *table_dev, const void *sr
 
 namespace {
 
-int group_range(const fst_plan *p, size_t group, bool slot, size_t &g0, size_t &g1)
+int group_range(const fst_plan *p, size_t group, int layout, size_t &g0, size_t &g1)
 {
     if (group == FST_ALL_GROUPS) {
-        if (slot) return fail(FST_E_ARG, "the slot layout takes one group at a time");
+        if (layout == FST_LAYOUT_SLOT) return fail(FST_E_ARG, "the slot layout takes one group at a time");
         g0 = 0;
         g1 = p->groups.size();
     } else {
@@ -139,11 +145,11 @@ int group_range(const fst_plan *p, size_t group, bool slot, size_t &g0, size_t &
 }
 
 // Builds the group's table and enqueues its upload into the workspace.  Caller holds image_mu.
-int prepare_locked(const fst_plan *p, size_t group, bool slot, size_t src_len, void *const *out_ptrs, void *ws,
+int prepare_locked(const fst_plan *p, size_t group, int layout, size_t src_len, void *const *out_ptrs, void *ws,
                    size_t ws_len, void *stream, bool builtin = false)
 {
     size_t g0, g1;
-    if (int rc = group_range(p, group, slot, g0, g1)) return rc;
+    if (int rc = group_range(p, group, layout, g0, g1)) return rc;
     TableImage &image = (builtin ? p->builtin_images : p->images)[group];
     image.dev = nullptr;
     size_t n_pieces = 0;
@@ -154,7 +160,7 @@ int prepare_locked(const fst_plan *p, size_t group, bool slot, size_t src_len, v
         return FST_OK;
     }
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
-    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, slot, image)) return rc;
+    if (int rc = build_image(p, g0, g1, out_ptrs, src_len, layout, image)) return rc;
     if (ws_len < image.blob.size())
         return fail(FST_E_RANGE, "workspace has %zu bytes, %zu needed", ws_len, image.blob.size());
     hipError_t e = hipMemcpyAsync(ws, image.blob.data(), image.blob.size(), hipMemcpyHostToDevice,
@@ -187,11 +193,11 @@ int launch_locked(const fst_plan *p, size_t group, const void *src_dev, size_t s
 }  // namespace
 
 int materialize_into(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
-                     void *ws, size_t ws_len, void *stream, bool slot, bool builtin)
+                     void *ws, size_t ws_len, void *stream, int layout, bool builtin)
 {
     if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_materialize: NULL argument");
     std::lock_guard<std::mutex> lock(p->image_mu);
-    if (int rc = prepare_locked(p, group, slot, src_len, out_ptrs, ws, ws_len, stream, builtin)) return rc;
+    if (int rc = prepare_locked(p, group, layout, src_len, out_ptrs, ws, ws_len, stream, builtin)) return rc;
     return launch_locked(p, group, src_dev, src_len, stream, builtin);
 }
 
@@ -210,9 +216,10 @@ int prepare_impl(const fst_plan *p, size_t group, int32_t layout, size_t src_len
                  size_t ws_len, void *stream)
 {
     if (!p || (!out_ptrs && !p->outputs.empty())) return fail(FST_E_ARG, "fst_prepare: NULL argument");
-    if (layout != FST_LAYOUT_RESIDENT && layout != FST_LAYOUT_SLOT) return fail(FST_E_ARG, "fst_prepare: unknown layout %d", layout);
+    if (layout != FST_LAYOUT_RESIDENT && layout != FST_LAYOUT_SLOT && layout != FST_LAYOUT_PACKED)
+        return fail(FST_E_ARG, "fst_prepare: unknown layout %d", layout);
     std::lock_guard<std::mutex> lock(p->image_mu);
-    return prepare_locked(p, group, layout == FST_LAYOUT_SLOT, src_len, out_ptrs, ws, ws_len, stream);
+    return prepare_locked(p, group, layout, src_len, out_ptrs, ws, ws_len, stream);
 }
 
 int launch_impl(const fst_plan *p, size_t group, const void *src_dev, size_t src_len, void *stream)
@@ -223,9 +230,9 @@ int launch_impl(const fst_plan *p, size_t group, const void *src_dev, size_t src
 }
 
 int materialize_impl(const void *src_dev, size_t src_len, const fst_plan *p, size_t group, void *const *out_ptrs,
-                     void *ws, size_t ws_len, void *stream, bool slot)
+                     void *ws, size_t ws_len, void *stream, int layout)
 {
-    return materialize_into(src_dev, src_len, p, group, out_ptrs, ws, ws_len, stream, slot, false);
+    return materialize_into(src_dev, src_len, p, group, out_ptrs, ws, ws_len, stream, layout, false);
 }
 
 }  // namespace
@@ -246,13 +253,13 @@ int fst_launch(const fst_plan *p, size_t group, const void *src_dev, size_t src_
 int fst_materialize(const void *raw_dev, size_t raw_len, const fst_plan *p, size_t group, void *const *out_ptrs,
                     void *dev_workspace, size_t workspace_len, void *stream)
 {
-    FST_GUARD(materialize_impl(raw_dev, raw_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, false));
+    FST_GUARD(materialize_impl(raw_dev, raw_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, FST_LAYOUT_RESIDENT));
 }
 
 int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *p, size_t group,
                          void *const *out_ptrs, void *dev_workspace, size_t workspace_len, void *stream)
 {
-    FST_GUARD(materialize_impl(slot_dev, slot_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, true));
+    FST_GUARD(materialize_impl(slot_dev, slot_len, p, group, out_ptrs, dev_workspace, workspace_len, stream, FST_LAYOUT_SLOT));
 }
 
 }  // extern "C"

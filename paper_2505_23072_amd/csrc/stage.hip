@@ -45,7 +45,9 @@ namespace {
 
 struct Block {
     uint32_t group, file;
-    uint64_t off, len;       // file range
+    uint64_t off, len;       // plain: file range [off, off+len).  Compacted: bytes [skip, skip+len) of the image of
+    uint64_t row_bytes;      //   the rows of row_bytes bytes that start at file offsets off, off+stride, ...
+    uint64_t stride, skip;   //   (stride 0 = plain)
     uint8_t *dst;            // device address
     bool first, last;        // of its group
 };
@@ -111,7 +113,21 @@ void reader(fst_stager *s, const std::vector<Block> *blocks, const std::vector<P
         int rc = 0;
         if (!skip_read) {
             const auto t0 = std::chrono::steady_clock::now();
-            rc = read(ctx, int32_t(b.file), b.off + pt.off, s->pinned + uint64_t(slot) * s->slot_bytes + pt.off, pt.len);
+            uint8_t *to = s->pinned + uint64_t(slot) * s->slot_bytes + pt.off;
+            if (b.stride == 0) {
+                rc = read(ctx, int32_t(b.file), b.off + pt.off, to, pt.len);
+            } else {
+                // compacted rows: one read per row segment, back to back into the ring slot
+                uint64_t pos = b.skip + pt.off, left = pt.len;
+                while (left && !rc) {
+                    const uint64_t r = pos / b.row_bytes, col = pos - r * b.row_bytes;
+                    const uint64_t n = std::min(b.row_bytes - col, left);
+                    rc = read(ctx, int32_t(b.file), b.off + r * b.stride + col, to, n);
+                    to += n;
+                    pos += n;
+                    left -= n;
+                }
+            }
             sh->read_ns += uint64_t(std::chrono::duration_cast<std::chrono::nanoseconds>(
                                         std::chrono::steady_clock::now() - t0).count());
         }
@@ -129,16 +145,22 @@ void reader(fst_stager *s, const std::vector<Block> *blocks, const std::vector<P
     }
 }
 
-int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, void *raw_dev, size_t raw_len,
+int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, int layout, void *raw_dev, size_t raw_len,
                void *const *slot_dev, size_t n_dev_slots, size_t dev_slot_bytes, void *const *out_ptrs, void *ws,
                size_t ws_len, uint32_t flags, fst_stage_stats *stats)
 {
-    const bool streamed = slot_dev != nullptr;
+    const bool streamed = layout == FST_LAYOUT_SLOT;
+    const bool packed = layout == FST_LAYOUT_PACKED;
     const bool kernels = !(flags & FST_STAGE_NO_KERNELS);
     const bool skip_read = (flags & FST_STAGE_NO_READ) != 0;
     if (!s || !p) return fail(FST_E_ARG, "fst_stage: NULL argument");
     if (!read && !skip_read) return fail(FST_E_ARG, "fst_stage: no read callback");
     if (kernels && !out_ptrs && !p->outputs.empty()) return fail(FST_E_ARG, "fst_stage: out_ptrs is NULL");
+    if (layout == FST_LAYOUT_RESIDENT && p->has_compact)
+        return fail(FST_E_ARG, "the plan's groups stage compacted rows: use the streamed or the packed load");
+    if (packed && raw_len < p->packed_bytes)
+        return fail(FST_E_RANGE, "the packed buffer has %zu bytes, the plan needs %llu", raw_len,
+                    (unsigned long long)p->packed_bytes);
     const size_t ng = p->groups.size();
     const double t_start = now_s();
 
@@ -155,12 +177,12 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
                             (unsigned long long)need, dev_slot_bytes);
             if (!slot_dev[g % n_dev_slots] || reinterpret_cast<uintptr_t>(slot_dev[g % n_dev_slots]) % FST_RAW_ALIGN)
                 return fail(FST_E_ALIGN, "device slot %zu is NULL or not %d-byte aligned", g % n_dev_slots, FST_RAW_ALIGN);
-        } else if (p->raw_base[gr.file] + gr.hi > raw_len) {
+        } else if (!packed && p->raw_base[gr.file] + gr.hi > raw_len) {
             return fail(FST_E_RANGE, "group %zu ends at byte %llu of a raw buffer of %zu", g,
                         (unsigned long long)(p->raw_base[gr.file] + gr.hi), raw_len);
         }
         if (kernels) {
-            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, streamed, images[g]))
+            if (int rc = build_image(p, g, g + 1, out_ptrs, streamed ? dev_slot_bytes : raw_len, layout, images[g]))
                 return rc;
             table_at[g] = all.size();                       // blobs are whole multiples of 256 bytes
             all.insert(all.end(), images[g].blob.begin(), images[g].blob.end());
@@ -168,7 +190,7 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
     }
     if (!streamed) {
         if (!raw_dev || reinterpret_cast<uintptr_t>(raw_dev) % FST_RAW_ALIGN)
-            return fail(FST_E_ALIGN, "raw buffer is NULL or not %d-byte aligned", FST_RAW_ALIGN);
+            return fail(FST_E_ALIGN, "%s buffer is NULL or not %d-byte aligned", packed ? "packed" : "raw", FST_RAW_ALIGN);
     }
     if (kernels && !all.empty()) {
         if (!ws || reinterpret_cast<uintptr_t>(ws) % 256) return fail(FST_E_ALIGN, "workspace is NULL or not 256-byte aligned");
@@ -184,10 +206,15 @@ int stage_impl(fst_stager *s, const fst_plan *p, fst_read_fn read, void *ctx, vo
         const size_t first_block = blocks.size();
         for (const Extent &ex : gr.extents) {
             uint8_t *base = streamed ? static_cast<uint8_t *>(slot_dev[g % n_dev_slots]) + ex.slot_off
+                            : packed ? static_cast<uint8_t *>(raw_dev) + gr.packed_off + ex.slot_off
                                      : static_cast<uint8_t *>(raw_dev) + p->raw_base[gr.file] + ex.lo;
-            for (uint64_t o = ex.lo; o < ex.hi; o += s->slot_bytes) {
-                const uint64_t len = std::min<uint64_t>(s->slot_bytes, ex.hi - o);
-                blocks.push_back(Block{uint32_t(g), gr.file, o, len, base + (o - ex.lo), false, false});
+            const uint64_t image = ex.image_bytes();
+            for (uint64_t o = 0; o < image; o += s->slot_bytes) {
+                const uint64_t len = std::min<uint64_t>(s->slot_bytes, image - o);
+                if (ex.compact())
+                    blocks.push_back(Block{uint32_t(g), gr.file, ex.lo, len, ex.row_bytes, ex.stride, o, base + o, false, false});
+                else
+                    blocks.push_back(Block{uint32_t(g), gr.file, ex.lo + o, len, 0, 0, 0, base + o, false, false});
             }
         }
         if (blocks.size() > first_block) {
@@ -360,8 +387,22 @@ int fst_stage_resident(fst_stager *s, const fst_plan *p, fst_read_fn read, void 
                        uint32_t flags, fst_stage_stats *stats)
 {
     try {
-        return stage_impl(s, p, read, read_ctx, raw_dev, raw_len, nullptr, 0, 0, out_ptrs, dev_workspace,
-                          workspace_len, flags, stats);
+        return stage_impl(s, p, read, read_ctx, FST_LAYOUT_RESIDENT, raw_dev, raw_len, nullptr, 0, 0, out_ptrs,
+                          dev_workspace, workspace_len, flags, stats);
+    } catch (const std::bad_alloc &) {
+        return fail(FST_E_NOMEM, "out of memory");
+    } catch (...) {
+        return fail(FST_E_ARG, "unexpected internal error");
+    }
+}
+
+int fst_stage_packed(fst_stager *s, const fst_plan *p, fst_read_fn read, void *read_ctx, void *packed_dev,
+                     size_t packed_len, void *const *out_ptrs, void *dev_workspace, size_t workspace_len,
+                     uint32_t flags, fst_stage_stats *stats)
+{
+    try {
+        return stage_impl(s, p, read, read_ctx, FST_LAYOUT_PACKED, packed_dev, packed_len, nullptr, 0, 0, out_ptrs,
+                          dev_workspace, workspace_len, flags, stats);
     } catch (const std::bad_alloc &) {
         return fail(FST_E_NOMEM, "out of memory");
     } catch (...) {
@@ -375,8 +416,8 @@ int fst_stage_streamed(fst_stager *s, const fst_plan *p, fst_read_fn read, void 
 {
     if (!slot_dev || n_dev_slots == 0) return fail(FST_E_ARG, "fst_stage_streamed: no device slots");
     try {
-        return stage_impl(s, p, read, read_ctx, nullptr, 0, slot_dev, n_dev_slots, dev_slot_bytes, out_ptrs,
-                          dev_workspace, workspace_len, flags, stats);
+        return stage_impl(s, p, read, read_ctx, FST_LAYOUT_SLOT, nullptr, 0, slot_dev, n_dev_slots, dev_slot_bytes,
+                          out_ptrs, dev_workspace, workspace_len, flags, stats);
     } catch (const std::bad_alloc &) {
         return fail(FST_E_NOMEM, "out of memory");
     } catch (...) {

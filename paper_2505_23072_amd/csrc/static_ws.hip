@@ -62,7 +62,7 @@ extern "C" int fst_materialize_static(const void *raw_dev, size_t raw_len, const
         void *ws = nullptr;
         if (int rc = scratch_address(&ws)) return rc;
         return fst::materialize_into(raw_dev, raw_len, p, group, out_ptrs, ws, FST_STATIC_WORKSPACE_BYTES, stream,
-                                     false, true);
+                                     FST_LAYOUT_RESIDENT, true);
     } catch (const std::bad_alloc &) {
         return fst::fail(FST_E_NOMEM, "out of memory");
     } catch (...) {

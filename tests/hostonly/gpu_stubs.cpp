@@ -13,6 +13,8 @@ void fst_stager_destroy(fst_stager *) {}
 int fst_read_fds(void *, int32_t, uint64_t, void *, uint64_t) { return -1; }
 int fst_stage_resident(fst_stager *, const fst_plan *, fst_read_fn, void *, void *, size_t, void *const *, void *, size_t,
                        uint32_t, fst_stage_stats *) { return FST_E_HIP; }
+int fst_stage_packed(fst_stager *, const fst_plan *, fst_read_fn, void *, void *, size_t, void *const *, void *, size_t,
+                     uint32_t, fst_stage_stats *) { return FST_E_HIP; }
 int fst_stage_streamed(fst_stager *, const fst_plan *, fst_read_fn, void *, void *const *, size_t, size_t, void *const *,
                        void *, size_t, uint32_t, fst_stage_stats *) { return FST_E_HIP; }
 }

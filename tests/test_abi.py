@@ -34,8 +34,8 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(B.fst_tensor_info) == 8 + 8 + 4 + 4 + 64 + 8 + 8
     assert ctypes.sizeof(B.fst_request) == 16
     assert ctypes.sizeof(B.fst_output_info) == 4 + 4 + 64 + 8 + 4 + 4
-    assert ctypes.sizeof(B.fst_group_info) == 4 * 4 + 8 * 6
-    assert ctypes.sizeof(B.fst_extent) == 24
+    assert ctypes.sizeof(B.fst_group_info) == 4 * 4 + 8 * 7
+    assert ctypes.sizeof(B.fst_extent) == 48
     assert ctypes.sizeof(B.fst_descriptor) == 12 + 8 + 4 + 8 * 5
     assert ctypes.sizeof(B.fst_stager_config) == 16
     assert ctypes.sizeof(B.fst_stage_stats) == 32

@@ -9,8 +9,8 @@ from paper_2505_23072_amd import binding as B
 from paper_2505_23072_amd import device
 from synth import writer
 from util_cases import FLOATS, cast_targets, make_file, random_bits, random_request
-from util_gpu import (first_diff, headers_of, materialize_resident, materialize_slots, oracle_outputs,
-                      upload_resident)
+from util_gpu import (first_diff, headers_of, materialize_packed, materialize_resident, materialize_slots,
+                      oracle_outputs, upload_resident)
 
 pytestmark = pytest.mark.gpu
 
@@ -44,6 +44,14 @@ def test_random_files(seed):
     _check(got, want, names, reqs, "sparse resident")
     got, _ = materialize_slots(blobs, names, reqs, rank, world, 32768, min_gap_bytes=300)
     _check(got, want, names, reqs, "sparse slots")
+    # strided shares staged as their row segments back to back (every segment of at least 2 / 64 bytes)
+    got, _ = materialize_slots(blobs, names, reqs, rank, world, 16384, min_gap_bytes=300, min_segment_bytes=2)
+    _check(got, want, names, reqs, "compacted slots")
+    got, plan = materialize_packed(blobs, names, reqs, rank, world, 1 << 16, min_gap_bytes=0, min_segment_bytes=64)
+    _check(got, want, names, reqs, "compacted, packed")
+    assert plan.packed_bytes() == sum(plan.group(g)["slot_bytes"] for g in range(plan.group_count()))
+    got, _ = materialize_packed(blobs, names, reqs, rank, world)
+    _check(got, want, names, reqs, "packed, one group per file")
 
 
 # several tiles (a tile is 16 KiB of output) and a ragged tail
@@ -163,6 +171,11 @@ def test_ragged_rows_of_at_least_one_chunk(residue):
             _check(got, want, names, reqs, f"world {world} rank {rank}")
             got, _ = materialize_slots([blob], names, reqs, rank, world, 1 << 20)
             _check(got, want, names, reqs, f"slots world {world} rank {rank}")
+            # groups cut between ragged rows: pieces that start off a 16-byte boundary of their output
+            got, plan = materialize_resident([blob], names, reqs, rank, world, max_group_bytes=40000, per_group=True)
+            _check(got, want, names, reqs, f"groups of 40000 bytes, world {world} rank {rank}")
+            got, _ = materialize_packed([blob], names, reqs, rank, world, 40000, min_gap_bytes=1 << 20, min_segment_bytes=16)
+            _check(got, want, names, reqs, f"compacted groups of 40000 bytes, world {world} rank {rank}")
 
 
 @pytest.mark.parametrize("src,dst", [("F16", "BF16"), ("BF16", "F16"), ("F16", "F32"), ("BF16", "F32")])
@@ -192,6 +205,79 @@ def test_f32_conversions_on_device(dst):
         got, _ = materialize_resident([blob], ["x"], [(dst, -1, 1)])
         want = orc.cast_array(x, "F32", dst).tobytes()
         assert got[0] == want, f"F32->{dst} lead {lead}: {first_diff(got[0], want)}"
+
+
+@pytest.mark.parametrize("residue", [0, 1, 2, 4, 13])
+def test_rows_shorter_than_a_chunk(residue):
+    """Partitions whose row segments are shorter than one chunk (1 to 15 bytes when copying, 1 to 7 elements when
+    converting): every chunk of the output is gathered from several rows.  Segment lengths and strides with
+    every power-of-two alignment (the kernel loads 4, 2 or 1 bytes at a time accordingly), several tiles,
+    every conversion, groups cut between rows."""
+    rng = np.random.default_rng(500 + residue)
+    # (name, dtype, shape, world): the share along the last dimension is shape[-1] / world elements
+    spec = [("a", "U8", (5000, 24), 8), ("b", "U8", (3001, 26), 2), ("c", "I16", (4100, 12), 4), ("d", "BF16", (2900, 8), 8),
+            ("e", "F32", (1500, 6), 2), ("f", "F16", (2050, 14), 2), ("g", "F64", (900, 6), 2), ("h", "I64", (700, 2), 2),
+            ("i", "BF16", (33, 7, 10), 5), ("j", "F32", (1100, 9), 3), ("k", "U8", (2000, 30), 2), ("l", "F64", (1200, 3), 3)]
+    ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
+    ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
+    blob = writer.write_file(None, ts, None, residue)
+    for world in (2, 3, 4, 5, 8):
+        names, reqs = [], []
+        for n, dt, shape, w in spec:
+            if w != world:
+                continue
+            for dst in [None] + cast_targets(dt):
+                names.append(n)
+                reqs.append((dst, len(shape) - 1, 1))
+        for rank in sorted({0, world - 1}):
+            print(f"residue {residue} world {world} rank {rank}: {len(names)} requests", flush=True)
+            want = oracle_outputs([blob], names, reqs, rank, world)
+            got, _ = materialize_resident([blob], names, reqs, rank, world)
+            _check(got, want, names, reqs, f"world {world} rank {rank}")
+            got, _ = materialize_resident([blob], names, reqs, rank, world, max_group_bytes=30000, per_group=True)
+            _check(got, want, names, reqs, f"groups of 30000 bytes, world {world} rank {rank}")
+            got, _ = materialize_slots([blob], names, reqs, rank, world, 1 << 20, min_gap_bytes=0)
+            _check(got, want, names, reqs, f"slots world {world} rank {rank}")
+
+
+def _f64_inputs_for_16bit(fmt):
+    """binary64 inputs around every rounding decision of a 16-bit format: for every pair of neighbouring
+    finite values their midpoint and the binary64 numbers next to it, exponents over and beyond the format's
+    range with the low mantissa bits cleared in a third of them, random patterns (NaNs included)."""
+    mb, bias = (10, 15) if fmt == "F16" else (7, 127)
+    rng = np.random.default_rng(17)
+    top = 0x7C00 if fmt == "F16" else 0x7F80
+    lo = np.arange(0, top - 1, dtype=np.uint16)
+    a = orc.cast_array(lo, fmt, "F64").view(np.float64)
+    b = orc.cast_array(lo + np.uint16(1), fmt, "F64").view(np.float64)
+    mid = (a + b) / 2
+    ties = np.concatenate([np.nextafter(mid, -np.inf), mid, np.nextafter(mid, np.inf)])
+    n = 1_000_000
+    e = rng.integers(1023 - bias - mb - 4, 1023 + bias + 4, n, dtype=np.uint64)
+    m = rng.integers(0, 1 << 52, n, dtype=np.uint64)
+    keep = rng.integers(52 - mb - 2, 53, n, dtype=np.uint64)
+    m = np.where(rng.random(n) < 0.33, (m >> keep) << keep, m)
+    sign = rng.integers(0, 2, n, dtype=np.uint64) << np.uint64(63)
+    return np.concatenate([ties.view(np.uint64), (-ties).view(np.uint64), sign | (e << np.uint64(52)) | m,
+                           rng.integers(0, 1 << 64, 500_000, dtype=np.uint64)])
+
+
+@pytest.mark.parametrize("fmt", ["F16", "BF16"])
+def test_binary64_and_16bit_conversions_on_device(fmt):
+    """binary64 -> binary16 / bfloat16 (one rounding from 53 bits) around every tie of the target format, and
+    the exact widenings of all 65536 patterns; sources at an aligned and at an odd offset."""
+    d = _f64_inputs_for_16bit(fmt)
+    allbits = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    print(f"{len(d)} binary64 inputs", flush=True)
+    want_d = orc.cast_array(d, "F64", fmt).tobytes()
+    want_w = orc.cast_array(allbits, fmt, "F64").tobytes()
+    for lead in (0, 3):
+        ts = [("lead", "U8", (lead,), bytes(lead)), ("d", "F64", (len(d),), d.tobytes()),
+              ("w", fmt, (1 << 16,), allbits.tobytes())]
+        blob = writer.write_file(None, ts, None, 0)
+        got, _ = materialize_resident([blob], ["d", "w"], [(fmt, -1, 1), ("F64", -1, 1)])
+        assert got[0] == want_d, f"F64->{fmt} lead {lead}: {first_diff(got[0], want_d)}"
+        assert got[1] == want_w, f"{fmt}->F64 lead {lead}: {first_diff(got[1], want_w)}"
 
 
 def test_binary64_conversions_on_device():

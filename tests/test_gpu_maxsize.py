@@ -1,8 +1,7 @@
 """Tensors longer than one kernel piece (a piece holds at most 2^31 chunks = 32 GiB of 16-byte chunks):
 the planner cuts them, and chunk indices stay below 2^31 inside every piece.  A launch class with more
-tiles than one dispatch can hold (4 194 048 tiles = 64 GiB - 4 MiB of 16-byte chunks) goes out as several
-dispatches.  The bytes come from the
-procedural source through the staging ring.  Every output byte is compared on the device with the raw
+workgroups than one dispatch can hold (4 194 048 workgroups = 64 GiB - 4 MiB of 16-byte chunks) goes out as
+several dispatches.  The bytes come from the procedural source through the staging ring.  Every output byte is compared on the device with the raw
 buffer itself (a whole-tensor copy and a column slice have plain definitions as array slices), and
 windows around the cut, the start and the end are compared with the oracle on the host."""
 import numpy as np
@@ -53,7 +52,7 @@ def test_one_row_of_65_gib_plus_a_ragged_tail():
         m = min(4 * GiB, n - at)
         assert torch.equal(out[at:at + m], raw[begin + at:begin + at + m]), f"bytes [{at}, {at + m}) differ"
     first_of_second_dispatch = 4194048 * 16384
-    # around the piece cuts, around the first tile of the second dispatch, and the ragged end, against the oracle
+    # around the piece cuts, around the first workgroup of the second dispatch, and the ragged end, against the oracle
     for at in (0, 32 * GiB - 4096, first_of_second_dispatch - 4096, 64 * GiB - 4096, n - 8192):
         stored = model.read(0, begin + at, 8192)
         want, _ = orc.materialize(stored, "U8", (8192,))

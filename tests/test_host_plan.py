@@ -30,7 +30,9 @@ def _interpret(plan, blobs):
         rb_s, rb_d = d["row_elems"] * es_s, d["row_elems"] * es_d
         for r in range(d["n_rows"]):
             lo = d["src_file_off"] + r * d["src_stride"]
-            assert any(e_lo <= lo and lo + rb_s <= e_hi for e_lo, e_hi, _ in g["extents"]), \
+            assert any((n == 1 and e_lo <= lo and lo + rb_s <= e_hi) or
+                       (n > 1 and lo >= e_lo and (lo - e_lo) % st + rb_s <= rb and (lo - e_lo) // st < n)
+                       for (e_lo, e_hi, _), (rb, n, st) in zip(g["extents"], g["extent_rows"])), \
                 "descriptor reads outside the staged extents of its group"
             row = src[lo:lo + rb_s]
             if d["src_dtype"] != d["dst_dtype"]:
@@ -77,30 +79,39 @@ def test_descriptors_reproduce_the_oracle(seed):
     bases = [4096 * 256 * i for i in range(nfiles)]
     plan = B.Plan(hs, bases, names, reqs, rank, world)
     want = _oracle_outputs(blobs, names, reqs, rank, world)
-    for max_bytes, gap in ((0, None), (4096, None), (20000, None), (1 << 20, None), (0, 0), (0, 4096), (8192, 0),
-                           (50000, 512), (1 << 20, 100000)):
-        ng = plan.set_groups(max_bytes, gap)
+    for max_bytes, gap, seg in ((0, None, None), (4096, None, None), (20000, None, None), (1 << 20, None, None),
+                                (0, 0, None), (0, 4096, None), (8192, 0, None), (50000, 512, None), (1 << 20, 100000, None),
+                                (0, 0, 1), (8192, 0, 16), (50000, 512, 64), (1 << 20, None, 2)):
+        ng = plan.set_groups(max_bytes, gap, seg)
         assert ng == plan.group_count()
         got = _interpret(plan, blobs)
         for i, (w, shape, dt) in enumerate(want):
             info = plan.output(i)
             assert info["shape"] == shape and info["dtype"] == dt and info["nbytes"] == len(w)
-            assert got[i] == w, (names[i], reqs[i], max_bytes)
+            assert got[i] == w, (names[i], reqs[i], max_bytes, gap, seg)
         rd = wr = 0
         for g in range(ng):
             gi = plan.group(g)
             assert gi["hi"] > gi["lo"] and gi["n_extents"] == len(gi["extents"]) >= 1
-            at = 0
-            for k, (lo, hi, off) in enumerate(gi["extents"]):
+            at, staged, prev_plain = 0, 0, None
+            for (lo, hi, off), (row_bytes, n_rows, stride) in zip(gi["extents"], gi["extent_rows"]):
                 assert hi > lo and off % 256 == lo % 256 and off >= at
-                if k:
-                    assert lo > gi["extents"][k - 1][1]
-                    if gap is not None:
-                        assert lo - gi["extents"][k - 1][1] > gap
-                at = off + hi - lo
-            assert gap is not None or gi["n_extents"] == 1
-            assert (gi["extents"][0][0], gi["extents"][-1][1]) == (gi["lo"], gi["hi"])
-            assert gi["staged_bytes"] == sum(hi - lo for lo, hi, _ in gi["extents"]) and at <= gi["slot_bytes"]
+                if n_rows == 1:                 # plain extents: ascending, apart by more than the gap, before the compacted ones
+                    assert row_bytes == hi - lo and stride == 0
+                    if prev_plain is not None:
+                        assert prev_plain != "compacted" and lo > prev_plain
+                        if gap is not None:
+                            assert lo - prev_plain > gap
+                    prev_plain = hi
+                else:
+                    assert seg is not None and row_bytes >= seg and stride > row_bytes
+                    assert hi == lo + (n_rows - 1) * stride + row_bytes
+                    prev_plain = "compacted"
+                staged += n_rows * row_bytes
+                at = off + n_rows * row_bytes
+            assert seg is not None or gap is not None or gi["n_extents"] == 1
+            assert (min(e[0] for e in gi["extents"]), max(e[1] for e in gi["extents"])) == (gi["lo"], gi["hi"])
+            assert gi["staged_bytes"] == staged and at <= gi["slot_bytes"]
             if max_bytes:
                 assert gi["slot_bytes"] <= max_bytes
             rd += gi["read_bytes"]
@@ -214,7 +225,7 @@ def test_plan_errors():
     assert err([h0], [0], ["x"], [(None, 0, 1)], rank=2, world=2) == "FST_E_SHARD"
     assert err([h0], [0], ["x"], [(None, 0, 1)], rank=0, world=0) == "FST_E_SHARD"
     assert err([h0], [0], ["i"], [("F16", -1, 1)]) == "FST_E_CAST"
-    assert err([h0], [0], ["x"], [("F64", -1, 1)]) == "FST_E_CAST"
+    assert err([h0], [0], ["x"], [("I16", -1, 1)]) == "FST_E_CAST"
     p = B.Plan([h0, h1], [0, 4096], ["x", "y", "i"], [("BF16", 0, 1), (None, 1, 1), (None, -1, 1)], 1, 2)
     with pytest.raises(B.FstError) as e:
         p.set_groups(100)

@@ -9,15 +9,12 @@ NP = {"U8": np.uint8, "I8": np.int8, "I16": np.int16, "U16": np.uint16, "F16": n
       "F8_E5M2": np.uint8, "F8_E4M3": np.uint8, "U32": np.uint32, "U64": np.uint64}
 ES = {k: np.dtype(v).itemsize for k, v in NP.items()}
 FLOATS = ("F32", "F16", "BF16")
+ALL_FLOATS = ("F64", "F32", "F16", "BF16")
 
 
 def cast_targets(dtype):
     """The element types a stored dtype can be converted to (other than itself)."""
-    if dtype == "F64":
-        return ["F32"]
-    if dtype == "F32":
-        return ["F16", "BF16", "F64"]
-    return [d for d in FLOATS if d != dtype] if dtype in FLOATS else []
+    return [d for d in ALL_FLOATS if d != dtype] if dtype in ALL_FLOATS else []
 
 
 def random_bits(rng, dtype, shape):
@@ -51,6 +48,8 @@ def random_request(rng, dtype, shape, world):
         dst = FLOATS[int(rng.integers(3))]
     elif dtype in ("F32", "F64") and rng.random() < 0.5:
         dst = "F64" if dtype == "F32" else "F32"
+    if dtype in ALL_FLOATS and rng.random() < 0.15:          # drawn last: the older cases keep their requests
+        dst = ALL_FLOATS[int(rng.integers(4))]
     dims = [d for d in range(len(shape)) if shape[d] % world == 0]
     if not dims or rng.random() < 0.25:
         return dst, -1, 1

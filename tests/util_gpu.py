@@ -64,11 +64,28 @@ def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=No
     return fetch(bufs, plan), plan
 
 
-def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_bytes=None):
+def slot_image(gi, blobs, fill=0xEE):
+    """The slot image of one group, built on the host from the file bytes: plain extents verbatim, compacted
+    extents as their row segments back to back; bytes between the extents keep `fill`."""
+    host = np.full(gi["slot_bytes"], fill, np.uint8)
+    data = np.frombuffer(blobs[gi["file"]], np.uint8)
+    for (lo, hi, off), (row_bytes, n_rows, stride) in zip(gi["extents"], gi["extent_rows"]):
+        assert off % 256 == lo % 256
+        if n_rows == 1:
+            assert row_bytes == hi - lo
+            host[off:off + hi - lo] = data[lo:hi]
+        else:
+            assert hi == lo + (n_rows - 1) * stride + row_bytes
+            for r in range(n_rows):
+                host[off + r * row_bytes:off + (r + 1) * row_bytes] = data[lo + r * stride:lo + r * stride + row_bytes]
+    return host
+
+
+def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_bytes=None, min_segment_bytes=None):
     """Slot layout: every group's extents alone in a slot buffer, each at its slot offset."""
     hs = headers_of(blobs)
     plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
-    plan.set_groups(max_group_bytes, min_gap_bytes)
+    plan.set_groups(max_group_bytes, min_gap_bytes, min_segment_bytes)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
         b.fill_(0x5A)
@@ -77,13 +94,36 @@ def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_
     for g in range(plan.group_count()):
         gi = plan.group(g)
         assert gi["slot_bytes"] <= max_group_bytes
-        host = np.full(gi["slot_bytes"], 0xEE, np.uint8)
-        for lo, hi, off in gi["extents"]:
-            assert off % 256 == lo % 256
-            host[off:off + hi - lo] = np.frombuffer(blobs[gi["file"]], np.uint8)[lo:hi]
-        slot[:gi["slot_bytes"]].copy_(torch.from_numpy(host))
+        slot[:gi["slot_bytes"]].copy_(torch.from_numpy(slot_image(gi, blobs)))
         B.fst_materialize_slot(slot.data_ptr(), gi["slot_bytes"], plan, g, ptrs, ws.data_ptr(), ws.numel(), 0)
         torch.cuda.synchronize()
+    return fetch(bufs, plan), plan
+
+
+def materialize_packed(blobs, names, reqs, rank=0, world=1, max_group_bytes=0, min_gap_bytes=None,
+                       min_segment_bytes=None):
+    """Packed layout: the slot images of all groups side by side in one buffer, one launch set for all."""
+    hs = headers_of(blobs)
+    plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
+    plan.set_groups(max_group_bytes, min_gap_bytes, min_segment_bytes)
+    bufs, ptrs = device.alloc_outputs(plan)
+    for b in bufs:
+        b.fill_(0x69)
+    ws = device.device_bytes(plan.workspace_bytes())
+    n = plan.packed_bytes()
+    host = np.full(max(n, 256), 0xEE, np.uint8)
+    at = 0
+    for g in range(plan.group_count()):
+        gi = plan.group(g)
+        assert gi["packed_offset"] == at and at % 256 == 0
+        host[at:at + gi["slot_bytes"]] = slot_image(gi, blobs)
+        at += gi["slot_bytes"]
+    assert at == n
+    packed = device.device_bytes(len(host))
+    packed.copy_(torch.from_numpy(host))
+    torch.cuda.synchronize()
+    B.fst_prepare(plan, B.FST_ALL_GROUPS, B.FST_LAYOUT_PACKED, n, ptrs, ws.data_ptr(), ws.numel(), 0)
+    B.fst_launch(plan, B.FST_ALL_GROUPS, packed.data_ptr(), n, 0)
     return fetch(bufs, plan), plan
 
 
