@@ -1,25 +1,36 @@
 #!/usr/bin/env python3
 """Benchmark of the device-side safetensors deserialization path on one MI355X.
 
-Default workload: the Llama-7B-shaped synthetic checkpoint (32 layers, hidden 4096, bf16, 13.48 GB
-in two files whose bodies start at byte residues 3 and 8 mod 16), materialized unchanged.  The other
-configurations (`--workload`) run the same legs with their own requests (conversion, one rank's
-partition); checkpoints too large for tmpfs come from the procedural byte source instead of files,
-and one larger than device memory is cut to its first `--layers` layers.
+Default run: the four large configurations, one after the other -- Llama-7B (materialize unchanged),
+Llama-13B (F16 -> BF16), Llama-70B rank 0 of 8 (dim-0 and dim-1 partitions), Bloom-176B rank 0 of 8
+(blocked fused-QKV, dim-0 and dim-1 partitions, layer norms widened to F32) -- all synthetic stand-ins with
+the paper's shapes and file splits.  The headline (`value`, `config`, `roofline`) is the largest, Bloom-176B;
+`per_config` carries the same figures for each.  Checkpoints that fit tmpfs are written there and read with
+pread; the larger ones come from the procedural byte source (bytes generated into the ring, nothing stored).
 
-One step = one pass of the hot path with the file bytes already resident in HBM: parse both headers,
-build the load plan, enqueue the materialize kernels for every group, wait.  `value` is
-(bytes read + bytes written by the kernels) / step time.  Around that the script also reports
-  * the end-to-end load (files in tmpfs -> pinned ring -> HBM -> tensors) against the pure
-    host-to-device copy of the same bytes,
-  * the roofline of the dominant kernel from HIP events on the launch stream,
-  * the CPU oracle timed on a bounded sample of the same checkpoint (baseline, not target).
+Per configuration:
+  * kernel leg -- one step = parse the headers + build the plan + upload the tables + run the materialize
+    kernels, with the staged bytes resident in HBM.  `--steps` steps are enqueued back to back (`value` =
+    bytes read + written by the kernels / step time: host work of step k+1 hides under the kernels of step
+    k), HIP events on the launch stream bracket the kernels of every step (roofline), and the same step is
+    timed again with a synchronisation after each one (`ms_per_step_sync`: what one load pays).
+    The raw bytes are held in the resident layout (whole files) when that fits device memory; Bloom-176B
+    (352 GB of files) is held in the packed layout with only the byte ranges rank 0 reads staged (gaps above
+    1 MiB left out; row-split tensors whole, so the kernels still take the column shares with strided reads).
+  * end-to-end leg -- source -> pinned ring -> HBM -> tensors, against the pure host-to-device copy of the
+    same staged bytes: warm (ring and buffers exist; best of `--e2e-reps`) and cold (ring creation, device
+    allocations, header parsing and planning included).  Tensor-parallel configurations stage sparsely and
+    with row segments compacted (`staging` says how), so what crosses PCIe is what the rank reads.
+  * `micro`: kernel-only figures for the paths the configurations do not reach (spliced, gathered, many
+    small tensors).
+The CPU oracle is timed on a bounded sample of the headline configuration (baseline, not target).
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes
+import gc
 import json
 import os
 import shutil
@@ -31,10 +42,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-
-
-PMC_SUMMARY = os.path.join(ROOT, "profiles", "materialize_vec_copy_llama7b_pmc.md")
+GIB = 1 << 30
+RESIDENT_LIMIT = 230 * GIB          # raw + outputs above this: hold the staged bytes in the packed layout instead
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "materialize_bloom176b_tp8_rank0_pmc.md")
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2505_23072_amd", "csrc", f) for f in ("kernels.hip", "fst_internal.h")]
+DEFAULT_WORKLOADS = "llama-7b,llama-13b,llama-70b,bloom-176b"
 
 
 def log(*a):
@@ -55,10 +67,10 @@ def kernel_sources_digest() -> str:
     return h.hexdigest()
 
 
-def recorded_traffic(kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size), or None when
-    there is no summary for this workload or the kernel sources (comments aside) changed after it was taken."""
+def recorded_traffic(workload: str):
+    """HBM bytes per launch set of `workload` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size), or None when there is
+    no summary for this workload or the kernel sources (comments aside) changed after it was taken."""
     try:
         text = open(PMC_SUMMARY).read()
     except OSError:
@@ -70,273 +82,8 @@ def recorded_traffic(kernel: str):
             fields[k.strip()] = v.strip()
     if fields.get("kernel_sources_sha256") != kernel_sources_digest():
         return None
-    v = fields.get(f"traffic_bytes_per_launch[{kernel}]")
+    v = fields.get(f"traffic_bytes_per_launch_set[{workload}]")
     return int(v) if v else None
-
-
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama-7b",
-                    choices=["llama-7b", "tiny", "llama-13b", "llama-70b", "bloom-176b", "falcon-40b"])
-    ap.add_argument("--layers", type=int, default=None,
-                    help="bloom-176b only: keep the first N layers (all 70 need 352 GB resident; default 22)")
-    ap.add_argument("--dir", default=None, help="where the synthetic files are written (default: tmpfs)")
-    ap.add_argument("--e2e-reps", type=int, default=3)
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU-baseline budget per leg")
-    ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-e2e", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
-    ap.add_argument("--all-ranks", action="store_true",
-                    help="tensor-parallel workloads: every rank's share of every split tensor from one plan and one "
-                         "launch set (replicated tensors once)")
-    ap.add_argument("--group-bytes", type=int, default=1 << 30)
-    ap.add_argument("--min-gap", type=int, default=None,
-                    help="end-to-end leg: do not stage unread file ranges longer than this many bytes "
-                         "(default: stage each group from its first to its last needed byte)")
-    ap.add_argument("--slots", type=int, default=8)
-    ap.add_argument("--slot-bytes", type=int, default=128 << 20)
-    ap.add_argument("--threads", type=int, default=12)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1", file=sys.stderr)
-        return 2
-
-    import numpy as np
-    import torch
-
-    from paper_2505_23072_amd import binding as B
-    from paper_2505_23072_amd import device
-    from synth import specs
-    from synth.source import ProceduralModel
-
-    dev = device.require_gpu()
-    B.lib()
-    cut = ""
-    if args.workload == "bloom-176b":
-        n_layers = args.layers or 22
-        spec = specs.config5_bloom176b(layers=n_layers)
-        cut = f" (first {n_layers} of 70 layers, embeddings and final norms: what fits resident)" if n_layers < 70 else ""
-    else:
-        spec = specs.CONFIGS[args.workload]()
-    t0 = time.time()
-    model = ProceduralModel(spec)
-    sizes = list(model.sizes)
-    from_files = sum(sizes) <= (32 << 30)
-    base_dir = args.dir or ("/dev/shm" if os.path.isdir("/dev/shm") else tempfile.gettempdir())
-    work = tempfile.mkdtemp(prefix="fst_bench_", dir=base_dir) if from_files else None
-    try:
-        if from_files:
-            paths = model.write_all(work, threads=16)
-            assert sizes == [os.path.getsize(p) for p in paths]
-            log(f"{spec.name}: {len(paths)} files, {sum(sizes) / 1e9:.2f} GB written to {work} in {time.time() - t0:.1f}s")
-        else:
-            paths = []
-            log(f"{spec.name}: {len(sizes)} files, {sum(sizes) / 1e9:.2f} GB from the procedural source (not stored)")
-        names, reqs = [], []
-        for f in spec.files:
-            for t in f.tensors:
-                ranks = range(spec.world) if args.all_ranks and t.shard_dim >= 0 else [-1]
-                for r in ranks:
-                    names.append(t.name)
-                    reqs.append((t.dst_dtype, t.shard_dim, t.blocks, r) if r >= 0 else (t.dst_dtype, t.shard_dim, t.blocks))
-        bases, raw_len = device.file_bases(sizes)
-
-        def parse_and_plan(group_bytes, min_gap=None):
-            if from_files:
-                hs = [device.read_header(p)[0] for p in paths]
-            else:
-                hs = [B.Header(h, n) for h, n in zip(model.headers, sizes)]
-            plan = B.Plan(hs, bases, names, reqs, spec.rank, spec.world)
-            plan.set_groups(group_bytes, min_gap)
-            return plan
-
-        plan = parse_and_plan(args.group_bytes, args.min_gap)
-        raw = device.device_bytes(raw_len, dev)
-        ws = device.device_bytes(plan.workspace_bytes(), dev)
-        bufs, ptrs = device.alloc_outputs(plan, dev)
-        rd, wr = plan.read_bytes(), plan.write_bytes()
-        log(f"plan: {plan.output_count()} outputs, {plan.group_count()} groups, read {rd / 1e9:.3f} GB, write {wr / 1e9:.3f} GB")
-
-        # ---------------- end-to-end: tmpfs (or procedural source) -> pinned ring -> HBM -> tensors
-        stager = B.Stager(args.slots, args.threads, args.slot_bytes)
-        fds = [os.open(p, os.O_RDONLY) for p in paths]
-        fd_arr = (ctypes.c_int * max(len(fds), 1))(*fds)
-        if from_files:
-            read_fn, ctx = B.read_fds_fn(), ctypes.addressof(fd_arr)
-        else:
-            read_fn, ctx = model.read_fn, model.ctx
-
-        def stage(flags):
-            return stager.stage_resident(plan, read_fn, ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(),
-                                         ws.numel(), flags)
-
-        e2e = {}
-        stage(B.FST_STAGE_NO_KERNELS)      # leaves the raw bytes resident for the timed steps below
-        if not args.no_e2e:
-            def best(flags):
-                ts = []
-                for _ in range(args.e2e_reps):
-                    t = time.perf_counter()
-                    s = stage(flags)
-                    ts.append((time.perf_counter() - t, s))
-                return min(ts, key=lambda x: x[0])
-            t_full, s_full = best(0)
-            t_stage, _ = best(B.FST_STAGE_NO_KERNELS)
-            t_h2d, _ = best(B.FST_STAGE_NO_KERNELS | B.FST_STAGE_NO_READ)
-            # the end-to-end figure includes header parsing and planning
-            t = time.perf_counter()
-            p2 = parse_and_plan(args.group_bytes, args.min_gap)
-            t_plan = time.perf_counter() - t
-            p2.close()
-            staged = s_full["staged_bytes"]
-            e2e = {
-                "end_to_end_s": round(t_full + t_plan, 4),
-                "parse_plan_s": round(t_plan, 5),
-                "stage_only_s": round(t_stage, 4),
-                "pure_h2d_s": round(t_h2d, 4),
-                "end_to_end_over_pure_h2d": round((t_full + t_plan) / t_h2d, 3),
-                "staged_gb": round(staged / 1e9, 3),
-                "h2d_gbps_pure": round(staged / t_h2d / 1e9, 2),
-                "h2d_gbps_end_to_end": round(staged / (t_full + t_plan) / 1e9, 2),
-                "reader_threads": args.threads, "ring": f"{args.slots}x{args.slot_bytes >> 20}MiB",
-                "staging": "whole groups" if args.min_gap is None else f"only the extents read (gaps > {args.min_gap} B skipped)",
-                "source": ("procedural byte source (bytes generated into the ring, nothing stored)" if not from_files
-                           else "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread"),
-            }
-            log("e2e", e2e)
-        for fd in fds:
-            os.close(fd)
-        stager.close()
-
-        if args.calibrate_copy:
-            # a plain device-to-device copy of known size (the runtime's own copy kernel): 4 GiB read
-            # and 4 GiB written per dispatch, the yardstick for the rocprofv3 --pmc byte counters
-            n_cal = 4 << 30
-            a = torch.empty(n_cal, dtype=torch.uint8, device=dev).fill_(7)
-            b = torch.empty(n_cal, dtype=torch.uint8, device=dev)
-            for _ in range(3):
-                b.copy_(a)
-            torch.cuda.synchronize()
-            del a, b
-
-        # ---------------- timed steps: raw bytes resident in HBM
-        stream = torch.cuda.Stream()
-        sp = stream.cuda_stream
-        plan.close()
-
-        # One step = parse + plan + table upload (fst_prepare) + kernels (fst_launch): what fst_materialize
-        # does, split so that HIP events on the launch stream bracket the kernels alone, inside the timed
-        # region.  With one group per file and few files every file is prepared and launched by itself
-        # (one kernel launch per file and conversion/alignment class: for the default workload exactly
-        # the two launches of a merged call); with many files all groups go in one merged launch set.
-        probe = parse_and_plan(0)
-        ng0 = probe.group_count()
-        groups = [probe.group(g) for g in range(ng0)]
-        plan_ws_bytes = probe.workspace_bytes()
-        probe.close()
-        per_group = ng0 <= 4
-        wss = [device.device_bytes(plan_ws_bytes, dev) for _ in range(ng0 if per_group else 1)]
-
-        def step(record):
-            p = parse_and_plan(0)
-            evs = []
-            with torch.cuda.stream(stream):
-                if per_group:
-                    for g in range(ng0):
-                        B.fst_prepare(p, g, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, wss[g].data_ptr(), wss[g].numel(), sp)
-                    for g in range(ng0):
-                        if record:
-                            evs.append(torch.cuda.Event(enable_timing=True))
-                            evs[-1].record(stream)
-                        B.fst_launch(p, g, raw.data_ptr(), raw_len, sp)
-                else:
-                    B.fst_prepare(p, B.FST_ALL_GROUPS, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, wss[0].data_ptr(),
-                                  wss[0].numel(), sp)
-                    if record:
-                        evs.append(torch.cuda.Event(enable_timing=True))
-                        evs[-1].record(stream)
-                    B.fst_launch(p, B.FST_ALL_GROUPS, raw.data_ptr(), raw_len, sp)
-                if record:
-                    evs.append(torch.cuda.Event(enable_timing=True))
-                    evs[-1].record(stream)
-            return p, evs
-
-        keep = []
-        for _ in range(args.warmup):
-            keep.append(step(False))
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(args.steps):
-            keep.append(step(True))
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t
-        ms_per_step = dt / args.steps * 1e3
-        value = (rd + wr) / (dt / args.steps) / 1e9
-        spans = [[evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)] for _, evs in keep if evs]
-        for p, _ in keep:
-            p.close()
-
-        # ---------------- roofline from the events of the timed steps
-        spans = np.array(spans)                       # [steps, launches per step]
-        if per_group:
-            nbytes = [g["read_bytes"] + g["write_bytes"] for g in groups]
-            dom = int(np.argmax(nbytes))
-            align = len(model.headers[groups[dom]["file"]]) % 16
-            if all(r[:3] == (None, -1, 1) for r in reqs):
-                kernel = "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>"
-            else:
-                kernel = "materialize kernels of the largest file (its conversions and partitions)"
-            launches = [{"file": groups[g]["file"], "source_residue_mod16": len(model.headers[groups[g]["file"]]) % 16,
-                         "bytes": nbytes[g], "ms_avg": round(float(spans[:, g].mean()), 4),
-                         "gbps": round(nbytes[g] / (spans[:, g].mean() * 1e-3) / 1e9, 1)} for g in range(ng0)]
-            dom_ms, dom_min, dom_bytes = float(spans[:, dom].mean()), float(spans[:, dom].min()), nbytes[dom]
-        else:
-            kernel = "all materialize kernels of one step (one merged launch set over every file)"
-            dom_ms, dom_min, dom_bytes = float(spans[:, 0].mean()), float(spans[:, 0].min()), rd + wr
-            launches = [{"files": "all", "bytes": dom_bytes, "ms_avg": round(dom_ms, 4),
-                         "gbps": round(dom_bytes / (dom_ms * 1e-3) / 1e9, 1)}]
-        achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-        roofline = {
-            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": recorded_traffic(kernel) if args.workload == "llama-7b" else None,
-            "kernel": kernel,
-            "launch_bytes": dom_bytes, "launch_ms_avg": round(dom_ms, 4), "launch_ms_min": round(dom_min, 4),
-            "timing": f"HIP events on the launch stream around fst_launch, in each of the {args.steps} timed steps",
-            "all_launches": launches,
-        }
-
-        # ---------------- CPU baseline: the oracle on a bounded sample of the same files
-        cpu = None
-        if not args.no_cpu:
-            cpu = cpu_baseline(model, spec, args.cpu_seconds)
-
-        out = {
-            "metric": "materialize GB/s (% of HBM peak) + end-to-end file->tensors seconds, 1 GPU",
-            "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "u8" if all(r[0] is None for r in reqs) else "u16", "data": "synthetic",
-            "config": {"workload": f"{spec.name}{cut}: {spec.n_tensors} tensors, {len(sizes)} files, {sum(sizes)} bytes, "
-                                   f"N(0,0.02), {describe_requests(spec)}"
-                                   + (f", all {spec.world} ranks' shares in one pass" if args.all_ranks and spec.world > 1 else ""),
-                       "bytes_read": rd, "bytes_written": wr,
-                       "step": "parse headers + plan + table upload + materialize kernels, raw bytes resident in HBM"},
-            "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-            "roofline": roofline,
-            "cpu_baseline": cpu,
-            "end_to_end": e2e,
-            "paper_context": "paper reports 4.8x-7.5x faster loading than safetensors 0.4.3 on 1-8 A100-80GB, PCIe Gen4, "
-                             "4 NVMe (end to end; no figure for the device-side step)",
-        }
-        print(json.dumps(out), flush=True)
-        return 0
-    finally:
-        if work:
-            shutil.rmtree(work, ignore_errors=True)
 
 
 def describe_requests(spec) -> str:
@@ -355,56 +102,520 @@ def describe_requests(spec) -> str:
     return ", ".join(parts)
 
 
-def cpu_baseline(model, spec, budget_s):
-    """The scalar oracle, as it is, over tensors of the first file in order until the time budget is used:
-    once on one thread, once fanned out over all host cores.  The stored bytes come from the same byte
-    source as the files (regenerated per tensor, untimed)."""
+def settle(freed_bytes: int, seconds: float) -> float:
+    """Idle wait after large device buffers have been freed.  For some seconds after a free of 100+ GB a
+    staged load (hundreds of host-to-device copies and kernel launches in flight) measured 30 % slower, with
+    or without kernels; it ran at full speed again when the process had idled for ten seconds first, when the
+    buffers had been kept instead of freed, and in a fresh process.  One configuration's clean-up must not be
+    charged to the next, so the benchmark waits before a configuration's first timed leg."""
+    if freed_bytes < (16 << 30) or seconds <= 0:
+        return 0.0
+    time.sleep(seconds)
+    return seconds
+
+
+class Workload:
+    """One synthetic checkpoint and its requests; everything a leg needs to build plans for it."""
+
+    def __init__(self, spec, args):
+        from paper_2505_23072_amd import binding as B
+        from synth.source import ProceduralModel
+        self.B, self.spec, self.args = B, spec, args
+        t0 = time.time()
+        self.model = ProceduralModel(spec)
+        self.sizes = list(self.model.sizes)
+        self.from_files = sum(self.sizes) <= (32 << 30) and not args.no_files
+        self.work = None
+        self.paths, self.fds = [], []
+        if self.from_files:
+            base_dir = args.dir or ("/dev/shm" if os.path.isdir("/dev/shm") else tempfile.gettempdir())
+            self.work = tempfile.mkdtemp(prefix="fst_bench_", dir=base_dir)
+            self.paths = self.model.write_all(self.work, threads=16)
+            assert self.sizes == [os.path.getsize(p) for p in self.paths]
+            self.fds = [os.open(p, os.O_RDONLY) for p in self.paths]
+            self.source = "tmpfs files, pread" if base_dir == "/dev/shm" else f"files in {base_dir}, pread"
+            log(f"{spec.name}: {len(self.paths)} files, {sum(self.sizes) / 1e9:.2f} GB written to {self.work} in {time.time() - t0:.1f}s")
+        else:
+            self.source = "procedural byte source (bytes generated into the ring, nothing stored)"
+            log(f"{spec.name}: {len(self.sizes)} files, {sum(self.sizes) / 1e9:.2f} GB from the procedural source (not stored)")
+        self.fd_arr = (ctypes.c_int * max(len(self.fds), 1))(*self.fds)
+        self.names, self.reqs = [], []
+        for f in spec.files:
+            for t in f.tensors:
+                self.names.append(t.name)
+                self.reqs.append((t.dst_dtype, t.shard_dim, t.blocks))
+
+    def read_callback(self):
+        if self.from_files:
+            return self.B.read_fds_fn(), ctypes.addressof(self.fd_arr)
+        return self.model.read_fn, self.model.ctx
+
+    def headers(self):
+        """Parsed from the bytes a loader would read first: the head of every file."""
+        from paper_2505_23072_amd import device
+        if self.from_files:
+            return [device.read_header(p)[0] for p in self.paths]
+        return [self.B.Header(h, n) for h, n in zip(self.model.headers, self.sizes)]
+
+    def plan(self, bases, group_bytes, min_gap=None, min_seg=None):
+        p = self.B.Plan(self.headers(), bases, self.names, self.reqs, self.spec.rank, self.spec.world)
+        p.set_groups(group_bytes, min_gap, min_seg)
+        return p
+
+    def close(self):
+        for fd in self.fds:
+            os.close(fd)
+        self.model.close()
+        if self.work:
+            shutil.rmtree(self.work, ignore_errors=True)
+
+
+def run_config(spec, args, freed_before, micro=False):
+    """All legs for one configuration; returns its dict of figures."""
+    import numpy as np
+    import torch
+
+    from paper_2505_23072_amd import binding as B
+    from paper_2505_23072_amd import device
+
+    dev = device.require_gpu()
+    w = Workload(spec, args)
+    try:
+        bases, raw_len = device.file_bases(w.sizes)
+        probe = w.plan(bases, 0)
+        out_bytes = probe.write_bytes()
+        rd, wr = probe.read_bytes(), probe.write_bytes()
+        n_outputs = probe.output_count()
+        probe.close()
+        tp = spec.world > 1
+        resident = raw_len + out_bytes <= RESIDENT_LIMIT
+        res = {"workload": f"{spec.name}: {spec.n_tensors} tensors, {len(w.sizes)} files, {sum(w.sizes)} bytes, N(0,0.02), "
+                           f"{describe_requests(spec)}",
+               "bytes_read": rd, "bytes_written": wr}
+
+        # ---------------- end-to-end: source -> pinned ring -> HBM -> tensors
+        # Tensor-parallel configurations stage only what the rank reads (gaps above 1 MiB skipped, row segments of
+        # at least 2 KiB compacted) into the packed layout; the others stage whole files into the resident layout.
+        e2e_gap, e2e_seg = (args.min_gap, args.min_segment) if tp else (None, None)
+        e2e_packed = tp
+
+        def e2e_plan():
+            return w.plan([0] * len(w.sizes) if e2e_packed else bases, args.group_bytes, e2e_gap, e2e_seg)
+
+        read_fn, ctx = w.read_callback()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        res["idle_before_s"] = settle(freed_before, args.settle_seconds)
+        if not args.no_e2e and not micro:
+            # cold: nothing exists yet but the source
+            t0 = time.perf_counter()
+            stager = B.Stager(args.slots, args.threads, args.slot_bytes)
+            plan = e2e_plan()
+            buf_len = plan.packed_bytes() if e2e_packed else raw_len
+            buf = device.device_bytes(buf_len, dev)
+            ws = device.device_bytes(plan.workspace_bytes(), dev)
+            bufs, ptrs = device.alloc_outputs(plan, dev)
+            torch.cuda.synchronize()
+
+            def stage(flags):
+                fn = stager.stage_packed if e2e_packed else stager.stage_resident
+                return fn(plan, read_fn, ctx, buf.data_ptr(), buf_len, ptrs, ws.data_ptr(), ws.numel(), flags)
+
+            s_cold = stage(0)
+            t_cold = time.perf_counter() - t0
+
+            def best(flags):
+                ts = []
+                for _ in range(args.e2e_reps):
+                    t = time.perf_counter()
+                    s = stage(flags)
+                    ts.append((time.perf_counter() - t, s))
+                log(spec.name, "stage flags", flags, "reps", [round(x[0], 4) for x in ts])
+                return min(ts, key=lambda x: x[0])
+
+            t_full, s_full = best(0)
+            t_stage, s_stage = best(B.FST_STAGE_NO_KERNELS)
+            t_h2d, _ = best(B.FST_STAGE_NO_KERNELS | B.FST_STAGE_NO_READ)
+            t = time.perf_counter()
+            p2 = e2e_plan()
+            t_plan = time.perf_counter() - t
+            p2.close()
+            staged = s_full["staged_bytes"]
+            res["end_to_end"] = {
+                "end_to_end_s": round(t_full + t_plan, 4),
+                "end_to_end_cold_s": round(t_cold, 4),
+                "cold_includes": "pinned ring creation, device allocations (raw, outputs, workspace), header parsing, planning",
+                "parse_plan_s": round(t_plan, 5),
+                "stage_only_s": round(t_stage, 4),
+                "pure_h2d_s": round(t_h2d, 4),
+                "end_to_end_over_pure_h2d": round((t_full + t_plan) / t_h2d, 3),
+                "staged_gb": round(staged / 1e9, 3),
+                "staged_over_bytes_read": round(staged / rd, 4),
+                "h2d_gbps_pure": round(staged / t_h2d / 1e9, 2),
+                "h2d_gbps_end_to_end": round(staged / (t_full + t_plan) / 1e9, 2),
+                "host_feed_gbps": round(staged / max(s_stage["seconds_read"] / args.threads, 1e-9) / 1e9, 2),
+                "reader_threads": args.threads, "ring": f"{args.slots}x{args.slot_bytes >> 20}MiB",
+                "staging": (f"packed layout: only the byte ranges the rank reads (gaps > {e2e_gap} B skipped), row "
+                            f"segments >= {e2e_seg} B read one by one and staged back to back" if tp
+                            else "resident layout: whole files"),
+                "source": w.source,
+            }
+            log(spec.name, "e2e", res["end_to_end"])
+            stager.close()
+            plan.close()
+            if e2e_packed or not resident:
+                buf = None                   # the kernel leg holds its own copy of the raw bytes
+            del ws
+            gc.collect()
+            torch.cuda.empty_cache()
+        else:
+            bufs = ptrs = buf = None
+
+        # ---------------- kernel leg: staged bytes resident in HBM
+        k_gap = None if resident else args.min_gap
+        k_bases = bases if resident else [0] * len(w.sizes)
+        layout = B.FST_LAYOUT_RESIDENT if resident else B.FST_LAYOUT_PACKED
+        plan = w.plan(k_bases, args.group_bytes, k_gap)
+        src_len = raw_len if resident else plan.packed_bytes()
+        if buf is None:
+            buf = device.device_bytes(src_len, dev)
+        if bufs is None:
+            bufs, ptrs = device.alloc_outputs(plan, dev)
+        ws = device.device_bytes(plan.workspace_bytes(), dev)
+        stager = B.Stager(args.slots, args.threads, args.slot_bytes)
+        torch.cuda.synchronize()
+        fn = stager.stage_resident if resident else stager.stage_packed
+        s = fn(plan, read_fn, ctx, buf.data_ptr(), src_len, ptrs, ws.data_ptr(), ws.numel(), B.FST_STAGE_NO_KERNELS)
+        stager.close()
+        res["kernel_leg_source"] = ("resident layout: whole files in HBM" if resident else
+                                    f"packed layout: the byte ranges the rank reads (gaps > {k_gap} B left out, row-split "
+                                    f"tensors whole: strided reads), {s['staged_bytes'] / 1e9:.1f} GB in HBM")
+        plan.close()
+
+        # One step = parse + plan + table upload (fst_prepare) + kernels (fst_launch): what fst_materialize does, split
+        # so that HIP events on the launch stream bracket the kernels alone, inside the timed region.  Few files: one
+        # group per file, every file prepared and launched by itself (per-file launch figures); many files: all groups
+        # in one merged launch set.
+        stream = torch.cuda.Stream()
+        sp = stream.cuda_stream
+        group_bytes = 0 if resident else args.group_bytes
+        probe = w.plan(k_bases, group_bytes, k_gap)
+        ng0 = probe.group_count()
+        groups = [probe.group(g) for g in range(ng0)]
+        ws_bytes = probe.workspace_bytes()
+        probe.close()
+        per_group = resident and ng0 <= 4
+        wss = [device.device_bytes(ws_bytes, dev) for _ in range(ng0 if per_group else 1)]
+
+        def step(record):
+            p = w.plan(k_bases, group_bytes, k_gap)
+            evs = []
+            with torch.cuda.stream(stream):
+                if per_group:
+                    for g in range(ng0):
+                        B.fst_prepare(p, g, layout, src_len, ptrs, wss[g].data_ptr(), wss[g].numel(), sp)
+                    for g in range(ng0):
+                        if record:
+                            evs.append(torch.cuda.Event(enable_timing=True))
+                            evs[-1].record(stream)
+                        B.fst_launch(p, g, buf.data_ptr(), src_len, sp)
+                else:
+                    B.fst_prepare(p, B.FST_ALL_GROUPS, layout, src_len, ptrs, wss[0].data_ptr(), wss[0].numel(), sp)
+                    if record:
+                        evs.append(torch.cuda.Event(enable_timing=True))
+                        evs[-1].record(stream)
+                    B.fst_launch(p, B.FST_ALL_GROUPS, buf.data_ptr(), src_len, sp)
+                if record:
+                    evs.append(torch.cuda.Event(enable_timing=True))
+                    evs[-1].record(stream)
+            return p, evs
+
+        keep = []
+        for _ in range(args.warmup):
+            keep.append(step(False))
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            keep.append(step(True))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        spans = np.array([[evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)] for _, evs in keep if evs])
+        for p, _ in keep:
+            p.close()
+        # the same step with a synchronisation after each one: the latency of a single load's device-side part
+        lat = []
+        for _ in range(max(3, args.steps // 2)):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            p, _ = step(False)
+            stream.synchronize()
+            lat.append(time.perf_counter() - t)
+            p.close()
+        ms_per_step = dt / args.steps * 1e3
+        ms_sync = float(np.median(lat)) * 1e3
+        res.update({
+            "value_gbps": round((rd + wr) / (dt / args.steps) / 1e9, 1),
+            "ms_per_step": round(ms_per_step, 4),
+            "ms_per_step_sync": round(ms_sync, 4),
+            "gbps_sync": round((rd + wr) / (ms_sync * 1e-3) / 1e9, 1),
+            "steps_enqueued": "back to back (host work of a step hides under the kernels of the one before)",
+        })
+
+        # ---------------- roofline from the events of the timed steps
+        if per_group:
+            nbytes = [g["read_bytes"] + g["write_bytes"] for g in groups]
+            dom = int(np.argmax(nbytes))
+            align = len(w.model.headers[groups[dom]["file"]]) % 16
+            if all(r[:3] == (None, -1, 1) for r in w.reqs):
+                kernel = "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>"
+            else:
+                kernel = "materialize kernels of the largest file (its conversions and partitions)"
+            launches = [{"file": groups[g]["file"], "source_residue_mod16": len(w.model.headers[groups[g]["file"]]) % 16,
+                         "bytes": nbytes[g], "ms_avg": round(float(spans[:, g].mean()), 4),
+                         "gbps": round(nbytes[g] / (spans[:, g].mean() * 1e-3) / 1e9, 1)} for g in range(ng0)]
+            dom_ms, dom_min, dom_bytes = float(spans[:, dom].mean()), float(spans[:, dom].min()), nbytes[dom]
+        else:
+            kernel = ("all materialize kernels of one step: one launch set over every file (materialize_vec<COPY> with "
+                      "byte- and dword-aligned sources carries the bytes; the conversions and tails are small launches)")
+            dom_ms, dom_min, dom_bytes = float(spans[:, 0].mean()), float(spans[:, 0].min()), rd + wr
+            launches = [{"files": "all", "bytes": dom_bytes, "ms_avg": round(dom_ms, 4),
+                         "gbps": round(dom_bytes / (dom_ms * 1e-3) / 1e9, 1)}]
+        achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+        res["roofline"] = {
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": recorded_traffic(spec.name),
+            "kernel": kernel,
+            "launch_bytes": dom_bytes, "launch_ms_avg": round(dom_ms, 4), "launch_ms_min": round(dom_min, 4),
+            "timing": f"HIP events on the launch stream around fst_launch, in each of the {args.steps} timed steps",
+            "all_launches": launches,
+        }
+        log(spec.name, {k: res[k] for k in ("value_gbps", "ms_per_step", "ms_per_step_sync")}, "kernels",
+            res["roofline"]["achieved"], "GB/s")
+        res["device_bytes_held"] = int(torch.cuda.max_memory_allocated())
+        del buf, bufs, wss, ws
+        gc.collect()
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+        return res, w
+    except BaseException:
+        w.close()
+        raise
+
+
+def micro_cases():
+    from synth import specs
+    return [
+        ("dim-1 share with 2050-byte row segments (spliced chunks), copy", specs.micro_ragged(), None),
+        ("the same, BF16 -> F32", specs.micro_ragged(dst="F32"), None),
+        ("the same, cut into groups of 64 MiB between ragged rows (pieces start inside a row)", specs.micro_ragged(), 64 << 20),
+        ("row segments of 4 of 32 bytes (gathered chunks; a line is fetched whole for an eighth of it)",
+         specs.micro_short_rows("BF16", 16, 8), None),
+        ("row segments of 8 of 16 bytes (gathered chunks)", specs.micro_short_rows("BF16", 8, 2), None),
+        ("row segments of 9 of 18 bytes (gathered chunks, byte loads)", specs.micro_short_rows("U8", 18, 2), None),
+        ("row segments of 2 of 16 bytes (gathered chunks)", specs.micro_short_rows("U8", 16, 8), None),
+        ("4096 tensors of 8 KiB, copy", specs.micro_small_tensors(), None),
+        ("4096 tensors of 8 KiB, BF16 -> F32", specs.micro_small_tensors(dst="F32"), None),
+        ("one tensor of 32 MiB, copy (the same bytes as 4096 x 8 KiB in one piece)", specs.micro_small_tensors(1, 1 << 24), None),
+    ]
+
+
+def run_micro(args):
+    """Kernel-only figures (HIP events around fst_launch, tables uploaded beforehand) for the kernel paths the
+    configurations do not reach."""
+    import numpy as np
+    import torch
+
+    from paper_2505_23072_amd import binding as B
+    from paper_2505_23072_amd import device
+
+    out = []
+    for title, spec, group_bytes in micro_cases():
+        w = Workload(spec, argparse.Namespace(**{**vars(args), "no_files": True}))
+        try:
+            bases, raw_len = device.file_bases(w.sizes)
+            plan = w.plan(bases, group_bytes or 0)
+            raw = device.device_bytes(raw_len)
+            ws = device.device_bytes(plan.workspace_bytes())
+            bufs, ptrs = device.alloc_outputs(plan)
+            st = B.Stager(8, args.threads, 32 << 20)
+            read_fn, ctx = w.read_callback()
+            st.stage_resident(plan, read_fn, ctx, raw.data_ptr(), raw_len, ptrs, ws.data_ptr(), ws.numel(), B.FST_STAGE_NO_KERNELS)
+            st.close()
+            stream = torch.cuda.Stream()
+            sp = stream.cuda_stream
+            B.fst_prepare(plan, B.FST_ALL_GROUPS, B.FST_LAYOUT_RESIDENT, raw_len, ptrs, ws.data_ptr(), ws.numel(), sp)
+            ms = []
+            for it in range(args.steps + 3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                B.fst_launch(plan, B.FST_ALL_GROUPS, raw.data_ptr(), raw_len, sp)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                if it >= 3:
+                    ms.append(e0.elapsed_time(e1))
+            rd, wr = plan.read_bytes(), plan.write_bytes()
+            m = float(np.mean(ms))
+            out.append({"case": title, "workload": spec.name, "bytes_read": rd, "bytes_written": wr,
+                        "groups": plan.group_count(), "ms_avg": round(m, 4), "ms_min": round(float(np.min(ms)), 4),
+                        "gbps": round((rd + wr) / (m * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round((rd + wr) / (m * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+            log("micro", out[-1])
+            plan.close()
+            del raw, bufs, ws
+        finally:
+            w.close()
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(w, budget_s):
+    """The scalar oracle, as it is, over tensors of one layer file of the configuration (its partitions and
+    conversions) in order until the time budget is used: once on one thread, once fanned out over all host
+    cores.  The stored bytes come from the same byte source as the files (regenerated per tensor, untimed)."""
     import numpy as np
 
     from oracle import oracle as orc
 
-    table = orc.parse(model.headers[0], model.sizes[0])
-    req = {t.name: t for t in spec.files[0].tensors}
+    model, spec = w.model, w.spec
+    fi = min(1, len(spec.files) - 1)                 # a layer file (file 0 of Bloom holds the embeddings alone)
+    table = orc.parse(model.headers[fi], model.sizes[fi])
+    req = {t.name: t for t in spec.files[fi].tensors}
     cores = len(os.sched_getaffinity(0))
 
     def jobs_for(tensors):
         js = []
         for t in tensors:
             r = req[t.name]
-            stored = model.read(0, table.body_off + t.begin, t.end - t.begin)      # into RAM, untimed
+            stored = model.read(fi, table.body_off + t.begin, t.end - t.begin)      # into RAM, untimed
             _, nb = orc.result_info(t.dtype, t.shape, r.dst_dtype, r.shard_dim, r.blocks, spec.rank, spec.world)
             js.append(dict(stored=stored, dtype=t.dtype, shape=t.shape, dst_dtype=r.dst_dtype, shard_dim=r.shard_dim,
                            blocks=r.blocks, rank=spec.rank, world=spec.world, out=np.empty(nb, np.uint8)))
         return js
 
-    # one thread: tensors in file order until the budget is spent
+    def moved(j):
+        """Algorithmic bytes of a job, counted like the kernels': the kept slice read + the output written."""
+        from synth.specs import DTYPE_SIZE
+        es_s, es_d = DTYPE_SIZE[j["dtype"]], DTYPE_SIZE[j["dst_dtype"] or j["dtype"]]
+        return j["out"].nbytes // es_d * es_s + j["out"].nbytes
+
+    # one thread: the file's tensors in order, again from the start when through, until the budget is spent
+    sel = list(table.tensors)
+    j = jobs_for(sel)
     done_bytes, t_used, k = 0, 0.0, 0
-    while k < len(table.tensors) and t_used < budget_s:
-        j = jobs_for([table.tensors[k]])
+    while t_used < budget_s:
+        one = [j[k % len(j)]]
         t = time.perf_counter()
-        orc.materialize_jobs(j, 1)
+        orc.materialize_jobs(one, 1)
         t_used += time.perf_counter() - t
-        done_bytes += j[0]["stored"].nbytes + j[0]["out"].nbytes
+        done_bytes += moved(one[0])
         k += 1
     single = done_bytes / t_used / 1e9
-    sample1 = f"first {k} tensors of file 1 ({done_bytes / 2e9:.2f} GB stored)"
-    # all cores: a sample sized from the single-thread rate
-    want = single * 1e9 * budget_s * min(cores, 8) / 2
-    sel, tot = [], 0
-    for t in table.tensors:
-        if tot >= want or tot > 16e9:
-            break
-        sel.append(t)
-        tot += t.end - t.begin
-    j = jobs_for(sel)
-    t = time.perf_counter()
-    orc.materialize_jobs(j, cores)
-    t_par = time.perf_counter() - t
-    par_bytes = sum(x["stored"].nbytes + x["out"].nbytes for x in j)
-    return {"value": round(par_bytes / t_par / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {len(sel)} tensors of file 1 ({tot / 1e9:.2f} GB stored), scalar oracle fanned out over "
-                      f"tensors on {cores} threads, {t_par:.1f}s",
+    sample1 = f"{k} tensors of file {fi + 1} in order (the file has {len(j)})"
+    # all cores: all tensors of the file per pass, passes until the budget is spent
+    per_pass = sum(moved(x) for x in j)
+    passes, t_par = 0, 0.0
+    while t_par < budget_s:
+        t = time.perf_counter()
+        orc.materialize_jobs(j, cores)
+        t_par += time.perf_counter() - t
+        passes += 1
+    return {"value": round(per_pass * passes / t_par / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{spec.name}: the {len(sel)} tensors of file {fi + 1} with the configuration's requests "
+                      f"({per_pass / 1e9:.2f} GB read + written), {passes} pass(es), scalar oracle fanned out over tensors on "
+                      f"{cores} threads, {t_par:.1f}s",
             "single_thread_value": round(single, 3), "single_thread_sample": sample1 + f", {t_used:.1f}s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workloads", "--workload", default=DEFAULT_WORKLOADS,
+                    help="comma-separated, run in this order; the last one is the headline "
+                         "(tiny, llama-7b, llama-13b, llama-70b, bloom-176b, falcon-40b)")
+    ap.add_argument("--dir", default=None, help="where the synthetic files are written (default: tmpfs)")
+    ap.add_argument("--no-files", action="store_true", help="never write files: every checkpoint from the procedural source")
+    ap.add_argument("--e2e-reps", type=int, default=3)
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU-baseline budget per leg")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-e2e", action="store_true")
+    ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--group-bytes", type=int, default=1 << 30)
+    ap.add_argument("--min-gap", type=int, default=1 << 20,
+                    help="sparse staging (tensor-parallel configurations): unread file ranges longer than this are not staged")
+    ap.add_argument("--min-segment", type=int, default=2048,
+                    help="compacted staging: row segments of at least this many bytes are read one by one")
+    ap.add_argument("--settle-seconds", type=float, default=10.0,
+                    help="idle wait before a configuration when the one before freed more than 16 GiB of device memory")
+    ap.add_argument("--slots", type=int, default=8)
+    ap.add_argument("--slot-bytes", type=int, default=128 << 20)
+    ap.add_argument("--threads", type=int, default=12)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the library has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2505_23072_amd import binding as B
+    from paper_2505_23072_amd import device
+    from synth import specs
+
+    device.require_gpu()
+    B.lib()
+    names = [n.strip() for n in args.workloads.split(",") if n.strip()]
+    per_config, cpu = [], None
+    freed = 0
+    for i, name in enumerate(names):
+        spec = specs.CONFIGS[name]()
+        res, w = run_config(spec, args, freed)
+        freed = res["device_bytes_held"]
+        try:
+            if i == len(names) - 1 and not args.no_cpu:
+                cpu = cpu_baseline(w, args.cpu_seconds)
+        finally:
+            w.close()
+        per_config.append(res)
+    micro = [] if args.no_micro else run_micro(args)
+
+    if args.calibrate_copy:
+        # a plain device-to-device copy of known size (the runtime's own copy kernel): 4 GiB read and 4 GiB
+        # written per dispatch, the yardstick for the rocprofv3 --pmc byte counters
+        n_cal = 4 << 30
+        a = torch.empty(n_cal, dtype=torch.uint8, device="cuda").fill_(7)
+        b = torch.empty(n_cal, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    head = per_config[-1]
+    head_spec = specs.CONFIGS[names[-1]]()
+    out = {
+        "metric": "materialize GB/s (% of HBM peak) + end-to-end file->tensors seconds, 1 GPU",
+        "value": head["value_gbps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8" if all(t.dst_dtype in (None, t.dtype) for f in head_spec.files for t in f.tensors) else "u16",
+        "data": "synthetic",
+        "config": {"workload": head["workload"], "bytes_read": head["bytes_read"], "bytes_written": head["bytes_written"],
+                   "step": "parse headers + plan + table upload + materialize kernels, staged bytes resident in HBM ("
+                           + head["kernel_leg_source"] + ")"},
+        "pct_of_hbm_peak": round(100.0 * head["value_gbps"] / HBM_PEAK_GBPS, 2),
+        "ms_per_step_sync": head["ms_per_step_sync"],
+        "roofline": head["roofline"],
+        "cpu_baseline": cpu,
+        "end_to_end": head.get("end_to_end", {}),
+        "per_config": per_config,
+        "micro": micro,
+        "paper_context": "paper reports 4.8x-7.5x faster loading than safetensors 0.4.3 on 1-8 A100-80GB, PCIe Gen4, "
+                         "4 NVMe (end to end; no figure for the device-side step)",
+    }
+    print(json.dumps(out), flush=True)
+    return 0
 
 
 if __name__ == "__main__":

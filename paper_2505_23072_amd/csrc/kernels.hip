@@ -525,13 +525,17 @@ struct WaveTile {
     uint32_t c0, n;
 };
 __device__ __forceinline__ bool wave_tile(const DevDesc *__restrict__ descs, const uint32_t *__restrict__ hints,
-                                          uint32_t wg_base, uint32_t n_tiles, WaveTile &wt)
+                                          uint32_t wg_base, WaveTile &wt)
 {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const uint32_t b = (wg_base + tile_of_workgroup(blockIdx.x, gridDim.x)) * WG_TILES + wave;
-    if (b >= n_tiles) return false;                                     // the launch's last workgroup may be short
+    // The launch's last workgroup may reach past the launch's last tile.  The hint table covers those
+    // tile indices too and leads them to the last piece, where they show as tiles past its end:
+    // telling them apart here, before the lookup, would put one more dependent scalar load (the
+    // tile count) in front of the wavefront's first memory access.
     wt.d = find_piece(descs, hints, b);
     const uint32_t t = b - wt.d.tile0();                                // tile inside the piece
+    if (t >= wt.d.n_tiles()) return false;
     wt.c0 = t * VEC_TILE_UNITS;                                         // a piece has at most 2^31 chunks
     // only a piece's last tile can be short; decided on 32-bit tile counts
     wt.n = (t + 1 == wt.d.n_tiles()) ? uint32_t(wt.d.n_units()) - wt.c0 : VEC_TILE_UNITS;
@@ -581,10 +585,10 @@ template <uint32_t CONV, bool BYTE>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs,
                                                                      const uint32_t *__restrict__ hints,
                                                                      const uint8_t *__restrict__ raw,
-                                                                     uint32_t wg_base, uint32_t n_tiles)
+                                                                     uint32_t wg_base)
 {
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, wt)) return;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane < wt.n)
         vec_chunk<CONV, BYTE>(raw + wt.d.src_off(), reinterpret_cast<uint8_t *>(wt.d.dst()), wt.c0 + lane, wt.d);
@@ -628,13 +632,13 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
                                                                         const uint8_t *__restrict__ raw,
-                                                                        uint32_t wg_base, uint32_t n_tiles)
+                                                                        uint32_t wg_base)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;                    // units per chunk
     constexpr uint32_t US = CS / CH;                                    // source bytes per unit
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, wt)) return;
     const PieceRegs &d = wt.d;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane >= wt.n) return;
@@ -707,13 +711,13 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_gather(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
                                                                         const uint8_t *__restrict__ raw,
-                                                                        uint32_t wg_base, uint32_t n_tiles)
+                                                                        uint32_t wg_base)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;
     constexpr uint32_t US = CS / CH;
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, n_tiles, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, wt)) return;
     const PieceRegs &d = wt.d;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane >= wt.n) return;
@@ -761,7 +765,7 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
                                                                        const uint32_t *__restrict__ hints,
                                                                        const uint8_t *__restrict__ raw,
-                                                                       uint32_t wg_base, uint32_t n_tiles)
+                                                                       uint32_t wg_base)
 {
     constexpr uint32_t ES = ConvTraits<CONV>::SRC / ConvTraits<CONV>::UNITS;         // bytes per source element
     constexpr uint32_t ED = ConvTraits<CONV>::DST / ConvTraits<CONV>::UNITS;
@@ -799,19 +803,19 @@ int launch_conv(uint32_t path, bool byte_aligned, const DevDesc *descs, const ui
         const uint32_t base = part.wg_base;
         if (path == PATH_VEC && !byte_aligned)
             hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base, n_tiles);
+                               base);
         else if (path == PATH_VEC)
             hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base, n_tiles);
+                               base);
         else if (path == PATH_SPLICE)
             hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base, n_tiles);
+                               base);
         else if (path == PATH_GATHER)
             hipLaunchKernelGGL((materialize_gather<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base, n_tiles);
+                               base);
         else
             hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base, n_tiles);
+                               base);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     }

@@ -98,12 +98,15 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         descs.push_back(d);
     }
     // hints: for every HINT_SPAN-th tile of a launch, the piece (counted from the launch's first)
-    // that holds it, and one more entry naming the launch's last piece
+    // that holds it, and one more entry naming the launch's last piece.  The table runs on over the
+    // tile indices that the launch's last workgroup has beyond the last tile: they lead to the last
+    // piece, where a wavefront sees that its tile lies past the piece's end.
     for (LaunchRange &r : ranges) {
         r.hint_first = uint32_t(image.hints.size());
+        const uint32_t padded = workgroups_of(class_path(r.cls), r.tiles) * (class_path(r.cls) == PATH_ELEM ? 1 : WG_TILES);
         uint32_t at = 0;
-        for (uint32_t t = 0; t < r.tiles; t += HINT_SPAN) {
-            while (t - descs[r.first + at].tile0 >= descs[r.first + at].n_tiles) ++at;
+        for (uint32_t t = 0; t < padded; t += HINT_SPAN) {
+            while (at + 1 < r.count && descs[r.first + at + 1].tile0 <= t) ++at;     // the last piece that starts at or before t
             image.hints.push_back(at);
         }
         image.hints.push_back(r.count - 1);

@@ -451,7 +451,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap, uint64_t min
         p->total_pieces += g.pieces.size();
         // a launch of k pieces with t_i tiles has ceil(sum t_i / HINT_SPAN) <= sum (t_i / HINT_SPAN + 1) hints,
         // plus its closing entry
-        g.hint_bound = N_CLASSES;               // the closing entry of every launch
+        g.hint_bound = 2 * N_CLASSES;           // per launch: the closing entry, and one for the last workgroup's spare tiles
         for (const Piece &pc : g.pieces)
             g.hint_bound += ceil_div(pc.n_units, tile_units(pc.path)) / HINT_SPAN + 1;
         p->read_bytes += g.read_bytes;

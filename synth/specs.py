@@ -241,6 +241,30 @@ def config_falcon40b(layers: int = 60, nfiles: int = 9, world: int = 2) -> Model
     return ModelSpec("falcon-40b", 6, files, world=world, rank=0)
 
 
+def micro_ragged(seg_bytes_x4: int = 8200, rows: int = 262144, dst: Optional[str] = None) -> ModelSpec:
+    """One bf16 matrix whose dim-1 share (rank 1 of 4) has row segments of seg_bytes_x4 / 4 bytes: 2050 by
+    default, not a multiple of 16 (a kernel-only case: spliced chunks)."""
+    cols = seg_bytes_x4 // 2
+    t = TensorSpec("w", "BF16", (rows, cols), shard_dim=1, dst_dtype=dst)
+    return ModelSpec(f"ragged-rows-{seg_bytes_x4 // 4}B" + (f"-to-{dst}" if dst else ""), 71,
+                     [FileSpec("a.safetensors", [t], 5)], world=4, rank=1)
+
+
+def micro_short_rows(dtype: str, cols: int, world: int, rows: int = 1 << 22) -> ModelSpec:
+    """One matrix with very short rows split along dim 1: the share's row segments are
+    cols / world elements, shorter than one 16-byte chunk (gathered chunks)."""
+    t = TensorSpec("w", dtype, (rows, cols), fill="normal" if dtype != "U8" else "bytes", shard_dim=1)
+    seg = cols // world * DTYPE_SIZE[dtype]
+    return ModelSpec(f"short-rows-{seg}B-of-{cols * DTYPE_SIZE[dtype]}B", 72, [FileSpec("a.safetensors", [t], 6)],
+                     world=world, rank=world - 1)
+
+
+def micro_small_tensors(n: int = 4096, elems: int = 4096, dst: Optional[str] = None) -> ModelSpec:
+    """n bf16 vectors of `elems` elements (8 KiB each by default) in one file."""
+    ts = [TensorSpec(f"t{i}", "BF16", (elems,), dst_dtype=dst) for i in range(n)]
+    return ModelSpec(f"{n}-tensors-of-{elems * 2}B" + (f"-to-{dst}" if dst else ""), 73, [FileSpec("a.safetensors", ts, 5)])
+
+
 CONFIGS = {
     "tiny": config1_tiny,
     "llama-7b": config2_llama7b,

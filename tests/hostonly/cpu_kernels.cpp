@@ -205,8 +205,7 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hin
             const uint32_t pos = part.wg_base + (path == PATH_ELEM ? blk : tile_of_workgroup(blk, part.n_wg));
             for (uint32_t wave = 0; wave < (path == PATH_ELEM ? 1u : WG_TILES); ++wave) {
                 const uint32_t b = path == PATH_ELEM ? pos : pos * WG_TILES + wave;
-                if (b >= n_tiles) continue;
-                if (seen[b]++) violation("tile visited twice", b, 0);
+                if (b < n_tiles && seen[b]++) violation("tile visited twice", b, 0);
                 // find_piece
                 uint32_t lo = hints[b / HINT_SPAN], hi = hints[b / HINT_SPAN + 1];
                 while (lo < hi) {
@@ -214,6 +213,10 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hin
                     if (descs[mid].tile0 <= b) lo = mid; else hi = mid - 1;
                 }
                 const DevDesc &d = descs[lo];
+                if (b >= n_tiles) {         // a spare tile of the last workgroup: must show as past the end of its piece
+                    if (b < d.tile0 || b - d.tile0 < d.n_tiles) violation("spare tile lands inside a piece", b, lo);
+                    continue;
+                }
                 if (b < d.tile0 || b - d.tile0 >= d.n_tiles) { violation("hint table names the wrong piece", b, lo); continue; }
                 const uint32_t t = b - d.tile0;
                 if (path == PATH_ELEM) { run_elem_tile(ci, d, raw, t); continue; }
