@@ -694,17 +694,17 @@ __device__ __forceinline__ void chunk_or(Chunk32 &c, uint32_t word, uint32_t v)
 
 // G consecutive source bytes of one row, starting at byte u of the piece's byte stream (copying).
 template <uint32_t G>
-__device__ __forceinline__ uint32_t gather_bytes(const uint8_t *base, const PieceRegs &d, uint32_t u)
+__device__ __forceinline__ uint64_t gather_bytes(const uint8_t *base, const PieceRegs &d, uint32_t u)
 {
     const uint32_t r = fast_div(u, d.div_m(), d.div_s());
-    return uint32_t(load_unit<G>(base + uint64_t(r) * d.src_stride() + (u - r * d.units_per_row())));
+    return load_unit<G>(base + uint64_t(r) * d.src_stride() + (u - r * d.units_per_row()));
 }
 
 // Gather path: rows shorter than one chunk (a partition along the last dimension of a tensor whose
 // rows are a few elements long).  As in the spliced path a lane owns one aligned chunk of the
 // output stream, but its units come from several rows, so it fetches them one by one: with loads
 // of `grain` bytes when the geometry keeps every source address a multiple of it (1, 2, 4 or 8
-// bytes; never more than one unit when converting), byte by byte otherwise.  The stores are
+// bytes; one element at a time when converting), byte by byte otherwise.  The stores are
 // full-width.  Neighbouring lanes read neighbouring rows, so every cache line is still fetched
 // once; what bounds this path is that a line is fetched whole for the few bytes kept of it.
 template <uint32_t CONV>
@@ -731,15 +731,22 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_gather(const De
     if (CONV == CONV_COPY) {
         // 16 bytes; rows, strides and the first address are multiples of `grain`, so `grain`
         // consecutive bytes never leave their row
-        if (grain >= 4) {
+        if (grain >= 8) {
 #pragma unroll
-            for (uint32_t j = 0; j < 4; ++j) chunk_or(v, j, gather_bytes<4>(base, d, u0 + 4 * j));
+            for (uint32_t j = 0; j < 2; ++j) {
+                const uint64_t e = gather_bytes<8>(base, d, u0 + 8 * j);
+                chunk_or(v, 2 * j, uint32_t(e));
+                chunk_or(v, 2 * j + 1, uint32_t(e >> 32));
+            }
+        } else if (grain == 4) {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) chunk_or(v, j, uint32_t(gather_bytes<4>(base, d, u0 + 4 * j)));
         } else if (grain == 2) {
 #pragma unroll
-            for (uint32_t j = 0; j < 8; ++j) chunk_or(v, j / 2, gather_bytes<2>(base, d, u0 + 2 * j) << (16 * (j % 2)));
+            for (uint32_t j = 0; j < 8; ++j) chunk_or(v, j / 2, uint32_t(gather_bytes<2>(base, d, u0 + 2 * j)) << (16 * (j % 2)));
         } else {
 #pragma unroll
-            for (uint32_t j = 0; j < 16; ++j) chunk_or(v, j / 4, gather_bytes<1>(base, d, u0 + j) << (8 * (j % 4)));
+            for (uint32_t j = 0; j < 16; ++j) chunk_or(v, j / 4, uint32_t(gather_bytes<1>(base, d, u0 + j)) << (8 * (j % 4)));
         }
     } else {
         const bool aligned = grain >= US;

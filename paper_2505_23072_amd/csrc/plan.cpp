@@ -129,9 +129,9 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
         const uint64_t addr = phase0 + soff;
         pc.dword_aligned = (addr % 4 == 0) && (nrows == 1 || stride % 4 == 0);
         if (path == PATH_GATHER) {
-            // the largest power of two (at most 8 bytes; 4 when copying, whose lanes load words) that divides the
-            // first address, the stride and the row length: loads of that size never straddle a row end
-            uint32_t grain = conv == CONV_COPY ? 4 : 8;
+            // the largest power of two (at most 8 bytes) that divides the first address, the stride and the row
+            // length: loads of that size never straddle a row end
+            uint32_t grain = 8;
             while (grain > 1 && (addr % grain || stride % grain || (upr * unit_s) % grain)) grain /= 2;
             pc.grain = grain;
         }

@@ -250,7 +250,7 @@ def micro_ragged(seg_bytes_x4: int = 8200, rows: int = 262144, dst: Optional[str
                      [FileSpec("a.safetensors", [t], 5)], world=4, rank=1)
 
 
-def micro_short_rows(dtype: str, cols: int, world: int, rows: int = 1 << 22) -> ModelSpec:
+def micro_short_rows(dtype: str, cols: int, world: int, rows: int = 1 << 24) -> ModelSpec:
     """One matrix with very short rows split along dim 1: the share's row segments are
     cols / world elements, shorter than one 16-byte chunk (gathered chunks)."""
     t = TensorSpec("w", dtype, (rows, cols), fill="normal" if dtype != "U8" else "bytes", shard_dim=1)

@@ -121,7 +121,7 @@ void run_chunk(uint32_t path, bool byte_variant, const ConvInfo &ci, const fst::
                 std::memcpy(buf + j * US, p, US);
             }
         } else {   // PATH_GATHER
-            const uint32_t step = ci.sd == ci.dd ? (d.grain >= 4 ? 4 : d.grain) : 1;       // units fetched per load
+            const uint32_t step = ci.sd == ci.dd ? d.grain : 1;                            // units fetched per load
             const uint32_t load_bytes = step * US;
             const bool aligned = ci.sd == ci.dd ? true : d.grain >= US;
             for (uint32_t j = 0; j < ci.ch; j += step) {

@@ -223,3 +223,119 @@ def test_falcon40b_tp2_rank0_streamed_sparse():
     whole = sum(t.nbytes for f in spec.files for t in f.tensors if t.shard_dim < 0)
     split = sum(t.nbytes for f in spec.files for t in f.tensors if t.shard_dim >= 0)
     assert plan.write_bytes() == whole + split // 2 == plan.read_bytes()
+
+
+def test_config4_through_the_loader_api(tmp_path):
+    """Llama-70B rank 0 of 8 through the paper-shaped Python API with the requests declared first: what crosses the
+    bus is what the sparse, compacted plan stages, every tensor equals the oracle's, and a loop of get_sharded /
+    get_tensor over all 723 keys costs microseconds per key.  The checkpoint is written to tmpfs three layers at a
+    time (files of 138 GB do not fit), so the loader runs once per slice of files."""
+    import os
+    import shutil
+    import tempfile
+
+    from paper_2505_23072_amd.loader import LocalShard, SafeTensorsFileLoader
+    spec = specs.config4_llama70b()
+    model = ProceduralModel(spec)
+    base = "/dev/shm" if os.path.isdir("/dev/shm") else str(tmp_path)
+    tabs = [orc.parse(h, s) for h, s in zip(model.headers, model.sizes)]
+    ld = SafeTensorsFileLoader(LocalShard(spec.rank, spec.world), torch.device("cuda:0"))
+    total_staged = total_read = n_keys = 0
+    t_fetch = 0.0
+    try:
+        for f0 in range(0, len(spec.files), 3):
+            work = tempfile.mkdtemp(prefix="fst_loader_", dir=base)
+            try:
+                fis = list(range(f0, min(f0 + 3, len(spec.files))))
+                paths = []
+                for fi in fis:
+                    p = os.path.join(work, spec.files[fi].filename)
+                    model.write_file(fi, p, 16)
+                    paths.append(p)
+                reqs = {t.name: (t.dst_dtype, t.shard_dim, t.blocks) for fi in fis for t in spec.files[fi].tensors}
+                ld.add_filenames({0: paths})
+                ld.add_requests(reqs)
+                fb = ld.copy_files_to_device()
+                probe = B.Plan([B.Header(model.headers[fi], model.sizes[fi]) for fi in fis], [0] * len(fis), list(reqs),
+                               list(reqs.values()), spec.rank, spec.world)
+                probe.set_groups(1 << 30, 1 << 20, 2048)
+                want_staged = sum(probe.group(g)["staged_bytes"] for g in range(probe.group_count()))
+                assert fb.staged_bytes == want_staged <= 1.01 * probe.read_bytes()
+                total_staged += fb.staged_bytes
+                total_read += probe.read_bytes()
+                probe.close()
+                t = time.perf_counter()
+                got = {n: (fb.get_sharded(n, rq[1], rq[0], rq[2]) if rq[1] >= 0 else fb.get_tensor(n, rq[0])) for n, rq in reqs.items()}
+                t_fetch += time.perf_counter() - t
+                n_keys += len(got)
+                jobs, keys = [], []
+                for fi in fis:
+                    for ts in spec.files[fi].tensors:
+                        t_ = tabs[fi].find(ts.name)
+                        stored = model.read(fi, tabs[fi].body_off + t_.begin, t_.end - t_.begin)
+                        dst, dim, blocks = reqs[ts.name]
+                        shape, nb = orc.result_info(t_.dtype, t_.shape, dst, dim, blocks, spec.rank, spec.world)
+                        assert tuple(got[ts.name].shape) == shape
+                        jobs.append(dict(stored=stored, dtype=t_.dtype, shape=t_.shape, dst_dtype=dst, shard_dim=dim, blocks=blocks,
+                                         rank=spec.rank, world=spec.world, out=np.empty(nb, np.uint8)))
+                        keys.append(ts.name)
+                orc.materialize_jobs(jobs, 16)
+                for k, j in zip(keys, jobs):
+                    g = got[k].contiguous().view(-1).view(torch.uint8).cpu().numpy()
+                    assert np.array_equal(g, j["out"]), k
+                fb.close()
+                del got, jobs
+            finally:
+                shutil.rmtree(work, ignore_errors=True)
+    finally:
+        ld.close()
+    assert n_keys == 723 and total_read == 18_163_974_144 and total_staged <= 1.01 * total_read
+    print(f"loader API, llama-70b rank 0/8: staged {total_staged / 1e9:.2f} GB for {total_read / 1e9:.2f} GB read; "
+          f"{n_keys} keys fetched in {t_fetch * 1e3:.2f} ms ({t_fetch / n_keys * 1e6:.1f} us per key)", flush=True)
+
+
+def test_config2_per_key_fetches_through_the_loader_api(tmp_path):
+    """Llama-7B the paper's way: whole files staged verbatim, then one get_tensor per key.  A fetch only
+    enqueues (tables in the library's built-in workspace, no wait), so the loop over all 291 keys is timed
+    separately from the kernels it queues; every tensor is then compared with the oracle."""
+    import os
+    import shutil
+    import tempfile
+
+    from paper_2505_23072_amd.loader import SafeTensorsFileLoader, SingleGroup
+    spec = specs.config2_llama7b()
+    model = ProceduralModel(spec)
+    base = "/dev/shm" if os.path.isdir("/dev/shm") else str(tmp_path)
+    work = tempfile.mkdtemp(prefix="fst_loader_", dir=base)
+    try:
+        paths = model.write_all(work, threads=16)
+        ld = SafeTensorsFileLoader(SingleGroup(), torch.device("cuda:0"))
+        ld.add_filenames({0: paths})
+        t = time.perf_counter()
+        fb = ld.copy_files_to_device()
+        t_copy = time.perf_counter() - t
+        names = [ts.name for f in spec.files for ts in f.tensors]
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        got = {n: fb.get_tensor(n) for n in names}
+        t_loop = time.perf_counter() - t
+        torch.cuda.synchronize()
+        t_all = time.perf_counter() - t
+        print(f"loader API, llama-7b: copy_files_to_device {t_copy:.3f}s; {len(names)} get_tensor calls enqueued in "
+              f"{t_loop * 1e3:.1f} ms ({t_loop / len(names) * 1e6:.0f} us per key), kernels done after {t_all * 1e3:.1f} ms", flush=True)
+        tabs = [orc.parse(h, s) for h, s in zip(model.headers, model.sizes)]
+        for fi, f in enumerate(spec.files):
+            jobs = []
+            for ts in f.tensors:
+                t_ = tabs[fi].find(ts.name)
+                stored = model.read(fi, tabs[fi].body_off + t_.begin, t_.end - t_.begin)
+                jobs.append(dict(stored=stored, dtype=t_.dtype, shape=t_.shape, dst_dtype=None, shard_dim=-1, blocks=1, rank=0,
+                                 world=1, out=np.empty(t_.end - t_.begin, np.uint8)))
+            orc.materialize_jobs(jobs, 16)
+            for ts, j in zip(f.tensors, jobs):
+                g = got[ts.name].contiguous().view(-1).view(torch.uint8).cpu().numpy()
+                assert np.array_equal(g, j["out"]), ts.name
+        fb.close()
+        ld.close()
+    finally:
+        shutil.rmtree(work, ignore_errors=True)

@@ -12,7 +12,8 @@ from paper_2505_23072_amd import binding as B
 from paper_2505_23072_amd import device
 from synth import specs
 from synth.source import ProceduralModel
-from util_cases import make_file, random_request
+from synth import writer
+from util_cases import make_file, random_bits, random_request
 from util_gpu import first_diff, headers_of, oracle_outputs
 
 pytestmark = pytest.mark.gpu
@@ -209,6 +210,59 @@ def test_loader_api(tmp_path):
         fb.get_tensor(names[0])
     loader.close()
     sh.close()
+
+
+def test_loader_with_declared_requests_stages_sparsely(tmp_path):
+    """Requests declared before copy_files_to_device: only the rank's bytes cross the bus (gaps skipped, row
+    segments compacted), resident-packed and streamed through small device slots; per-key fetches on two
+    streams in turn (they share the library's built-in workspace) without a wait in between."""
+    from paper_2505_23072_amd.loader import LocalShard, SafeTensorsFileLoader
+    rng = np.random.default_rng(61)
+    ts = [("emb", "BF16", (512, 256)), ("q", "BF16", (1024, 256)), ("o", "BF16", (256, 2048)), ("qkv", "F16", (3 * 256, 128)),
+          ("n", "BF16", (256,)), ("r", "F32", (300, 274)), ("u", "BF16", (4096, 256)), ("d", "BF16", (256, 4096))]
+    full = [(n, d, s, random_bits(rng, d, s).tobytes()) for n, d, s in ts]
+    path = str(tmp_path / "m.safetensors")
+    blob = writer.write_file(path, full, None, 9)
+    reqs = {"emb": (None, -1, 1), "q": (None, 0, 1), "o": (None, 1, 1), "qkv": ("F32", 0, 3), "n": ("F32", -1, 1),
+            "r": ("BF16", 1, 1), "u": (None, 0, 1), "d": (None, 1, 1)}
+    world, rank = 2, 1
+    want = oracle_outputs([blob], list(reqs), list(reqs.values()), rank, world)
+    probe = B.Plan(headers_of([blob]), [0], list(reqs), list(reqs.values()), rank, world)
+    read_bytes = probe.read_bytes()
+    probe.close()
+    for slots in (None, (2, 1 << 18)):
+        ld = SafeTensorsFileLoader(LocalShard(rank, world), torch.device("cuda:0"), bounce_buffer_bytes=1 << 16,
+                                   min_gap_bytes=4096, min_segment_bytes=256, group_bytes=1 << 20)
+        ld.add_filenames({0: [path]})
+        ld.add_requests(reqs)
+        fb = ld.copy_files_to_device(stream_slots=slots)
+        # what crossed the bus is what the rank reads (plus nothing: every gap here is above min_gap, every
+        # row segment above min_segment)
+        assert fb.staged_bytes == read_bytes, (fb.staged_bytes, read_bytes, slots)
+        assert fb.staged_bytes < 0.6 * len(blob)
+        for (n, rq), w in zip(reqs.items(), want):
+            t = fb.get_sharded(n, rq[1], rq[0], rq[2]) if rq[1] >= 0 else fb.get_tensor(n, rq[0])
+            assert t.contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes() == w, (n, slots)
+        with pytest.raises(RuntimeError):       # not declared, and the raw bytes were never resident
+            fb.get_sharded("q", 1)
+        fb.close()
+        ld.close()
+    # undeclared: whole files resident; fetches alternate between two streams and never wait
+    ld = SafeTensorsFileLoader(LocalShard(rank, world), torch.device("cuda:0"))
+    ld.add_filenames({0: [path]})
+    fb = ld.copy_files_to_device()
+    assert fb.staged_bytes == len(blob) - headers_of([blob])[0].body_offset()      # every tensor byte, once
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = {}
+    for rep in range(3):
+        for k, (n, rq) in enumerate(reqs.items()):
+            with torch.cuda.stream(streams[(k + rep) % 2]):
+                got[n] = fb.get_many({n: rq})[n]
+    torch.cuda.synchronize()
+    for (n, rq), w in zip(reqs.items(), want):
+        assert got[n].contiguous().view(-1).view(torch.uint8).cpu().numpy().tobytes() == w, n
+    fb.close()
+    ld.close()
 
 
 def test_files_written_by_the_safetensors_package(tmp_path):
