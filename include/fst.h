@@ -299,7 +299,7 @@ int fst_materialize_slot(const void *slot_dev, size_t slot_len, const fst_plan *
  * workspace of FST_STATIC_WORKSPACE_BYTES that is built into the library (one per GPU, held until
  * the process ends) instead of a caller-allocated one; the call allocates and frees no device
  * memory.  FST_E_RANGE, before anything is enqueued, when the tables of `group` (or of all groups)
- * may not fit: a piece takes 64 bytes and every MiB of output 4 more.  Every call on a GPU uses
+ * may not fit: a piece takes 96 bytes and every MiB of output 8 more.  Every call on a GPU uses
  * that GPU's one workspace and overwrites what the previous call left there: calls on one stream
  * are ordered; calls that overlap on different streams of one GPU race, as do calls from several
  * threads.  Everything else (arguments, checks, kernels, results) is fst_materialize's.

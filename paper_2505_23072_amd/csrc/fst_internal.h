@@ -163,13 +163,21 @@ inline uint32_t workgroups_of(uint32_t path, uint32_t n_tiles)
 // tile-by-tile interleaving and giving each XCD one contiguous eighth.
 constexpr uint32_t XCD_COUNT = 8;
 constexpr uint32_t XCD_RUN = 32;
-// A wavefront finds its piece through a hint table with one entry per HINT_SPAN tiles (1 MiB of
-// 16-byte chunks; the piece that holds the span's first tile) plus a closing entry per launch (its
-// last piece): the owner of a tile lies between its span's entry and the next one; for large
-// tensors the two coincide.  Spans of 256 KiB measured 3 % slower on large tensors with a
-// byte-aligned source (more distinct table lines for the scalar cache), spans of 2 to 16 MiB the
-// same as 1 MiB.
-constexpr uint32_t HINT_SPAN = 1024;
+// A wavefront finds its piece through a hint table with one entry per span of 2^hint_shift tiles
+// (the piece that holds the span's first tile) plus a closing entry per launch (its last piece): the
+// owner of a tile lies between its span's entry and the next one; when they coincide (a span inside
+// one tensor) nothing is searched.  The span is chosen per launch, about the launch's mean piece
+// length but at most 1024 tiles (1 MiB of 16-byte chunks): on large tensors spans of 256 KiB
+// measured 3 % slower than 1 MiB with a byte-aligned source (more distinct table lines for the
+// scalar cache) and spans of 2 to 16 MiB the same, while a launch of thousands of 8 KiB tensors gets
+// spans of 8 tiles and one search step at most.
+constexpr uint32_t MAX_HINT_SHIFT = 10;
+inline uint32_t hint_shift_for(uint32_t n_tiles, uint32_t n_pieces)
+{
+    uint32_t shift = 0;
+    while (shift < MAX_HINT_SHIFT && (uint64_t(2) << shift) * n_pieces <= n_tiles) ++shift;
+    return shift;
+}
 // The work-item count of one dispatch (workgroups x workgroup size) must fit 32 bits, so a launch
 // class with more workgroups than MAX_LAUNCH_WORKGROUPS goes out as several launches, each with
 // the index of its first workgroup as an argument.  The limit is a whole number of permutation
@@ -217,14 +225,14 @@ inline uint32_t conv_store_align(uint32_t conv) { return conv == CONV_D2H || con
 
 // One kernel launch: pieces [first, first+count) of a device table, all of one launch class, with
 // their hint entries [hint_first, ...).
-struct LaunchRange { uint32_t cls, first, count, tiles, hint_first; };
+struct LaunchRange { uint32_t cls, first, count, tiles, hint_first, hint_shift; };
 inline uint32_t class_path(uint32_t cls) { return cls < CONV_COUNT * 2 ? uint32_t(PATH_VEC) : cls / CONV_COUNT - 1; }
 inline uint32_t class_conv(uint32_t cls) { return cls < CONV_COUNT * 2 ? cls / 2 : cls % CONV_COUNT; }
 // Host copy of a device table: pieces, hints, and the launches over them.
 struct TableImage {
     std::vector<DevDesc> descs;
-    std::vector<uint32_t> hints;      // per launch: for tile HINT_SPAN*k, the piece (from the launch's first) holding it,
-                                      //   then the launch's last piece
+    std::vector<uint32_t> hints;      // per launch: for every span of tiles the piece (counted from the launch's first)
+                                      //   holding the span's first tile, then the launch's last piece
     std::vector<LaunchRange> ranges;
     std::vector<uint8_t> blob;        // what is copied to the device: descs, then hints at table_hint_offset
     // set by fst_prepare: where the blob was uploaded and the source length it was checked against
@@ -279,5 +287,5 @@ int materialize_into(const void *src_dev, size_t src_len, const fst_plan *p, siz
                      void *ws, size_t ws_len, void *stream, int layout, bool builtin);
 // Launch the kernels of one class.  descs_dev / hints_dev: the class's arrays on the device.
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
-                         const void *raw_dev, void *stream);
+                         uint32_t hint_shift, const void *raw_dev, void *stream);
 }  // namespace fst

@@ -493,14 +493,15 @@ static_assert(offsetof(DevDesc, src_off) == 0 && offsetof(DevDesc, src_stride) =
               offsetof(DevDesc, div_s) == 48 && offsetof(DevDesc, unit0) == 52 && offsetof(DevDesc, grain) == 56,
               "PieceRegs reads DevDesc by dword position");
 
-// The piece that owns tile `b`.  hints[k] names the piece that holds tile k*HINT_SPAN (the last
-// piece for the entry past the end), so the owner lies between hints[b/HINT_SPAN] and the next
-// entry: for a large tensor the two are equal and nothing is searched; a span full of small
-// tensors costs a binary search over first-tile fields, at most log2(HINT_SPAN) steps.
+// The piece that owns tile `b`.  hints[k] names the piece that holds the first tile of span k (a span
+// is 2^shift tiles; past the end: the last piece), so the owner lies between hints[b >> shift] and
+// the next entry: for a span inside one tensor the two are equal and nothing is searched; a span
+// that holds several small tensors costs a binary search over first-tile fields (the host picks the
+// span so that it holds two pieces at most on average).
 __device__ __forceinline__ PieceRegs find_piece(const DevDesc *__restrict__ descs,
-                                                const uint32_t *__restrict__ hints, uint32_t b)
+                                                const uint32_t *__restrict__ hints, uint32_t b, uint32_t shift)
 {
-    uint32_t lo = hints[b / HINT_SPAN], hi = hints[b / HINT_SPAN + 1];
+    uint32_t lo = hints[b >> shift], hi = hints[(b >> shift) + 1];
     while (lo < hi) {
         const uint32_t mid = (lo + hi + 1) >> 1;
         if (descs[mid].tile0 <= b) lo = mid; else hi = mid - 1;
@@ -525,7 +526,7 @@ struct WaveTile {
     uint32_t c0, n;
 };
 __device__ __forceinline__ bool wave_tile(const DevDesc *__restrict__ descs, const uint32_t *__restrict__ hints,
-                                          uint32_t wg_base, WaveTile &wt)
+                                          uint32_t wg_base, uint32_t hint_shift, WaveTile &wt)
 {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const uint32_t b = (wg_base + tile_of_workgroup(blockIdx.x, gridDim.x)) * WG_TILES + wave;
@@ -533,7 +534,7 @@ __device__ __forceinline__ bool wave_tile(const DevDesc *__restrict__ descs, con
     // tile indices too and leads them to the last piece, where they show as tiles past its end:
     // telling them apart here, before the lookup, would put one more dependent scalar load (the
     // tile count) in front of the wavefront's first memory access.
-    wt.d = find_piece(descs, hints, b);
+    wt.d = find_piece(descs, hints, b, hint_shift);
     const uint32_t t = b - wt.d.tile0();                                // tile inside the piece
     if (t >= wt.d.n_tiles()) return false;
     wt.c0 = t * VEC_TILE_UNITS;                                         // a piece has at most 2^31 chunks
@@ -585,10 +586,10 @@ template <uint32_t CONV, bool BYTE>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_vec(const DevDesc *__restrict__ descs,
                                                                      const uint32_t *__restrict__ hints,
                                                                      const uint8_t *__restrict__ raw,
-                                                                     uint32_t wg_base)
+                                                                     uint32_t wg_base, uint32_t hint_shift)
 {
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, hint_shift, wt)) return;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane < wt.n)
         vec_chunk<CONV, BYTE>(raw + wt.d.src_off(), reinterpret_cast<uint8_t *>(wt.d.dst()), wt.c0 + lane, wt.d);
@@ -632,13 +633,13 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
                                                                         const uint8_t *__restrict__ raw,
-                                                                        uint32_t wg_base)
+                                                                        uint32_t wg_base, uint32_t hint_shift)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;                    // units per chunk
     constexpr uint32_t US = CS / CH;                                    // source bytes per unit
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, hint_shift, wt)) return;
     const PieceRegs &d = wt.d;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane >= wt.n) return;
@@ -711,13 +712,13 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_gather(const DevDesc *__restrict__ descs,
                                                                         const uint32_t *__restrict__ hints,
                                                                         const uint8_t *__restrict__ raw,
-                                                                        uint32_t wg_base)
+                                                                        uint32_t wg_base, uint32_t hint_shift)
 {
     constexpr uint32_t CS = ConvTraits<CONV>::SRC, CD = ConvTraits<CONV>::DST;
     constexpr uint32_t CH = ConvTraits<CONV>::UNITS;
     constexpr uint32_t US = CS / CH;
     WaveTile wt;
-    if (!wave_tile(descs, hints, wg_base, wt)) return;
+    if (!wave_tile(descs, hints, wg_base, hint_shift, wt)) return;
     const PieceRegs &d = wt.d;
     const uint32_t lane = threadIdx.x % WAVE;
     if (lane >= wt.n) return;
@@ -772,12 +773,12 @@ template <uint32_t CONV>
 __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const DevDesc *__restrict__ descs,
                                                                        const uint32_t *__restrict__ hints,
                                                                        const uint8_t *__restrict__ raw,
-                                                                       uint32_t wg_base)
+                                                                       uint32_t wg_base, uint32_t hint_shift)
 {
     constexpr uint32_t ES = ConvTraits<CONV>::SRC / ConvTraits<CONV>::UNITS;         // bytes per source element
     constexpr uint32_t ED = ConvTraits<CONV>::DST / ConvTraits<CONV>::UNITS;
     const uint32_t b = wg_base + blockIdx.x;                                         // one tile per workgroup
-    const PieceRegs d = find_piece(descs, hints, b);
+    const PieceRegs d = find_piece(descs, hints, b, hint_shift);
     const uint32_t t = b - d.tile0();
     const uint64_t e0 = uint64_t(t) * ELEM_TILE_UNITS;
     const uint32_t n = (t + 1 == d.n_tiles()) ? uint32_t(d.n_units() - e0) : ELEM_TILE_UNITS;
@@ -803,26 +804,26 @@ __global__ __launch_bounds__(ELEM_BLOCK_THREADS) void materialize_elem(const Dev
 
 template <uint32_t CONV>
 int launch_conv(uint32_t path, bool byte_aligned, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles,
-                const uint8_t *raw, hipStream_t stream)
+                uint32_t hint_shift, const uint8_t *raw, hipStream_t stream)
 {
     for (const LaunchPart &part : split_launch(workgroups_of(path, n_tiles))) {
         const dim3 grid(part.n_wg);
         const uint32_t base = part.wg_base;
         if (path == PATH_VEC && !byte_aligned)
             hipLaunchKernelGGL((materialize_vec<CONV, false>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base);
+                               base, hint_shift);
         else if (path == PATH_VEC)
             hipLaunchKernelGGL((materialize_vec<CONV, true>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base);
+                               base, hint_shift);
         else if (path == PATH_SPLICE)
             hipLaunchKernelGGL((materialize_splice<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base);
+                               base, hint_shift);
         else if (path == PATH_GATHER)
             hipLaunchKernelGGL((materialize_gather<CONV>), grid, dim3(VEC_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base);
+                               base, hint_shift);
         else
             hipLaunchKernelGGL((materialize_elem<CONV>), grid, dim3(ELEM_BLOCK_THREADS), 0, stream, descs, hints, raw,
-                               base);
+                               base, hint_shift);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(FST_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     }
@@ -832,7 +833,7 @@ int launch_conv(uint32_t path, bool byte_aligned, const DevDesc *descs, const ui
 }  // namespace
 
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
-                         const void *raw_dev, void *stream)
+                         uint32_t hint_shift, const void *raw_dev, void *stream)
 {
     if (n_tiles == 0) return FST_OK;
     if (cls >= N_CLASSES) return fail(FST_E_ARG, "unknown launch class %u", cls);
@@ -841,19 +842,19 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
     const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (conv) {
-    case CONV_COPY: return launch_conv<CONV_COPY>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_H2B: return launch_conv<CONV_H2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_B2H: return launch_conv<CONV_B2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_H2F: return launch_conv<CONV_H2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_B2F: return launch_conv<CONV_B2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2H: return launch_conv<CONV_F2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2B: return launch_conv<CONV_F2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_D2F: return launch_conv<CONV_D2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_F2D: return launch_conv<CONV_F2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_D2H: return launch_conv<CONV_D2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_D2B: return launch_conv<CONV_D2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_H2D: return launch_conv<CONV_H2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
-    case CONV_B2D: return launch_conv<CONV_B2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, raw, s);
+    case CONV_COPY: return launch_conv<CONV_COPY>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_H2B: return launch_conv<CONV_H2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_B2H: return launch_conv<CONV_B2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_H2F: return launch_conv<CONV_H2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_B2F: return launch_conv<CONV_B2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_F2H: return launch_conv<CONV_F2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_F2B: return launch_conv<CONV_F2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_D2F: return launch_conv<CONV_D2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_F2D: return launch_conv<CONV_F2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_D2H: return launch_conv<CONV_D2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_D2B: return launch_conv<CONV_D2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_H2D: return launch_conv<CONV_H2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_B2D: return launch_conv<CONV_B2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
     default: return fail(FST_E_ARG, "unknown launch class %u", cls);
     }
 }

@@ -97,16 +97,21 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         r.count += 1;
         descs.push_back(d);
     }
-    // hints: for every HINT_SPAN-th tile of a launch, the piece (counted from the launch's first)
-    // that holds it, and one more entry naming the launch's last piece.  The table runs on over the
-    // tile indices that the launch's last workgroup has beyond the last tile: they lead to the last
-    // piece, where a wavefront sees that its tile lies past the piece's end.
+    // hints: for every span of 2^hint_shift tiles of a launch, the piece (counted from the launch's
+    // first) that holds the span's first tile, and one more entry naming the launch's last piece.  The
+    // table runs on over the tile indices that the launch's last workgroup has beyond the last tile:
+    // they lead to the last piece, where a wavefront sees that its tile lies past the piece's end.
+    // (A table of pairs -- the owners of a span's first and last tile, which would spare small
+    // tensors that fill their spans exactly the one search step -- measured 6 to 11 % slower on large
+    // tensors.)
     for (LaunchRange &r : ranges) {
         r.hint_first = uint32_t(image.hints.size());
+        r.hint_shift = hint_shift_for(r.tiles, r.count);
         const uint32_t padded = workgroups_of(class_path(r.cls), r.tiles) * (class_path(r.cls) == PATH_ELEM ? 1 : WG_TILES);
-        uint32_t at = 0;
-        for (uint32_t t = 0; t < padded; t += HINT_SPAN) {
-            while (at + 1 < r.count && descs[r.first + at + 1].tile0 <= t) ++at;     // the last piece that starts at or before t
+        const uint32_t span = 1u << r.hint_shift;
+        uint32_t at = 0;                            // the last piece that starts at or before the span's first tile
+        for (uint32_t t = 0; t < padded; t += span) {
+            while (at + 1 < r.count && descs[r.first + at + 1].tile0 <= t) ++at;
             image.hints.push_back(at);
         }
         image.hints.push_back(r.count - 1);
@@ -126,7 +131,7 @@ int launch_ranges(const TableImage &image, const void *table_dev, const void *sr
     const uint32_t *hints = reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(table_dev) +
                                                                table_hint_offset(image.descs.size()));
     for (const LaunchRange &r : image.ranges)
-        if (int rc = launch_class_kernels(r.cls, descs + r.first, hints + r.hint_first, r.tiles, src_dev, stream))
+        if (int rc = launch_class_kernels(r.cls, descs + r.first, hints + r.hint_first, r.tiles, r.hint_shift, src_dev, stream))
             return rc;
     return FST_OK;
 }

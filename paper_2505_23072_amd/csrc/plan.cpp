@@ -449,11 +449,12 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap, uint64_t min
     for (Group &g : G) {
         p->max_group_pieces = std::max(p->max_group_pieces, g.pieces.size());
         p->total_pieces += g.pieces.size();
-        // a launch of k pieces with t_i tiles has ceil(sum t_i / HINT_SPAN) <= sum (t_i / HINT_SPAN + 1) hints,
-        // plus its closing entry
-        g.hint_bound = 2 * N_CLASSES;           // per launch: the closing entry, and one for the last workgroup's spare tiles
+        // a launch of k pieces and T tiles has at most T / 1024 + 2k + 2 spans (hint_shift_for: below the
+        // largest shift a span is longer than half the mean piece), the last workgroup's spare tiles included,
+        // and two table entries per span
+        g.hint_bound = 4 * N_CLASSES;
         for (const Piece &pc : g.pieces)
-            g.hint_bound += ceil_div(pc.n_units, tile_units(pc.path)) / HINT_SPAN + 1;
+            g.hint_bound += 2 * (ceil_div(pc.n_units, tile_units(pc.path)) >> MAX_HINT_SHIFT) + 8;
         p->read_bytes += g.read_bytes;
         p->write_bytes += g.write_bytes;
         g.packed_off = packed;

@@ -21,7 +21,7 @@ struct Range { uintptr_t lo, hi; };
 std::mutex g_mu;
 Range g_source{0, 0};
 std::vector<Range> g_outputs;
-uint64_t g_chunks = 0, g_violations = 0;
+uint64_t g_chunks = 0, g_violations = 0, g_direct = 0;   // g_direct: tiles whose piece took one search step at most
 char g_first_violation[256] = "";
 
 void violation(const char *what, uint64_t a, uint64_t b)
@@ -176,7 +176,7 @@ void fst_test_clear_outputs(void)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     g_outputs.clear();
-    g_chunks = g_violations = 0;
+    g_chunks = g_violations = g_direct = 0;
     g_first_violation[0] = 0;
 }
 void fst_test_add_output(const void *p, uint64_t len)
@@ -185,13 +185,14 @@ void fst_test_add_output(const void *p, uint64_t len)
     g_outputs.push_back({uintptr_t(p), uintptr_t(p) + len});
 }
 uint64_t fst_test_violations(void) { return g_violations; }
+uint64_t fst_test_direct_tiles(void) { return g_direct; }
 const char *fst_test_first_violation(void) { return g_first_violation; }
 }
 
 namespace fst {
 
-int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles, const void *raw_dev,
-                         void *)
+int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hints, uint32_t n_tiles, uint32_t hint_shift,
+                         const void *raw_dev, void *)
 {
     if (n_tiles == 0) return FST_OK;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -207,7 +208,8 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hin
                 const uint32_t b = path == PATH_ELEM ? pos : pos * WG_TILES + wave;
                 if (b < n_tiles && seen[b]++) violation("tile visited twice", b, 0);
                 // find_piece
-                uint32_t lo = hints[b / HINT_SPAN], hi = hints[b / HINT_SPAN + 1];
+                uint32_t lo = hints[b >> hint_shift], hi = hints[(b >> hint_shift) + 1];
+                if (b < n_tiles && hi - lo <= 1) ++g_direct;
                 while (lo < hi) {
                     const uint32_t mid = (lo + hi + 1) >> 1;
                     if (descs[mid].tile0 <= b) lo = mid; else hi = mid - 1;

@@ -141,7 +141,7 @@ namespace fst {
 
 // The launch as the race detector sees it: on the launch's stream, one read per piece from the
 // source buffer and one write per piece to its output.
-int launch_class_kernels(uint32_t, const DevDesc *descs_dev, const uint32_t *, uint32_t n_tiles, const void *raw_dev,
+int launch_class_kernels(uint32_t, const DevDesc *descs_dev, const uint32_t *, uint32_t n_tiles, uint32_t, const void *raw_dev,
                          void *stream)
 {
     if (n_tiles == 0) return FST_OK;

@@ -20,6 +20,7 @@ L.fst_test_set_source.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
 L.fst_test_add_output.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
 L.fst_test_first_violation.restype = ctypes.c_char_p
 L.fst_test_violations.restype = ctypes.c_uint64
+L.fst_test_direct_tiles.restype = ctypes.c_uint64
 
 
 def aligned(n, fill):
@@ -278,3 +279,18 @@ def test_staging_with_compacted_extents():
         for i, w in enumerate(want):
             assert outs[i].tobytes() == w, f"{mode} {group_bytes} {min_gap} {min_seg}: output {i} {names[i]} {reqs[i]}"
         plan.close()
+
+
+def test_hint_spans_follow_the_piece_length():
+    """512 tensors of 8 KiB (8 tiles each): the launch's hint spans are 8 tiles long, so every tile finds its
+    piece with one search step at most; one large tensor keeps spans of 1024 tiles."""
+    ts = [(f"t{i}", "BF16", (4096,), bytes(8192)) for i in range(512)]
+    blob = writer.write_file(None, ts, None, 0)
+    names = [t[0] for t in ts]
+    got, plan = run([blob], names, [(None, -1, 1)] * len(names), 0, 1, layout=B.FST_LAYOUT_RESIDENT)
+    assert L.fst_test_direct_tiles() == 512 * 8
+    plan.close()
+    blob = writer.write_file(None, [("big", "U8", (3 << 20,), bytes(3 << 20)), ("small", "U8", (100,), bytes(100))], None, 0)
+    got, plan = run([blob], ["big", "small"], [(None, -1, 1)] * 2, 0, 1, layout=B.FST_LAYOUT_RESIDENT)
+    assert L.fst_test_direct_tiles() >= 3072 - 1024
+    plan.close()
