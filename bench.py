@@ -142,8 +142,11 @@ class Workload:
         self.names, self.reqs = [], []
         for f in spec.files:
             for t in f.tensors:
-                self.names.append(t.name)
-                self.reqs.append((t.dst_dtype, t.shard_dim, t.blocks))
+                # --all-ranks: one request per (tensor, rank) for the split tensors, replicated tensors once
+                ranks = range(spec.world) if getattr(args, "all_ranks", False) and t.shard_dim >= 0 else [-1]
+                for r in ranks:
+                    self.names.append(t.name)
+                    self.reqs.append((t.dst_dtype, t.shard_dim, t.blocks, r) if r >= 0 else (t.dst_dtype, t.shard_dim, t.blocks))
 
     def read_callback(self):
         if self.from_files:
@@ -190,7 +193,8 @@ def run_config(spec, args, freed_before, micro=False):
         tp = spec.world > 1
         resident = raw_len + out_bytes <= RESIDENT_LIMIT
         res = {"workload": f"{spec.name}: {spec.n_tensors} tensors, {len(w.sizes)} files, {sum(w.sizes)} bytes, N(0,0.02), "
-                           f"{describe_requests(spec)}",
+                           f"{describe_requests(spec)}"
+                           + (f", all {spec.world} ranks' shares in one pass" if args.all_ranks and spec.world > 1 else ""),
                "bytes_read": rd, "bytes_written": wr}
 
         # ---------------- end-to-end: source -> pinned ring -> HBM -> tensors
@@ -206,7 +210,7 @@ def run_config(spec, args, freed_before, micro=False):
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
         res["idle_before_s"] = settle(freed_before, args.settle_seconds)
-        if not args.no_e2e and not micro:
+        if not args.no_e2e and not micro and not args.all_ranks:
             # cold: nothing exists yet but the source
             t0 = time.perf_counter()
             stager = B.Stager(args.slots, args.threads, args.slot_bytes)
@@ -542,6 +546,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--all-ranks", action="store_true",
+                    help="tensor-parallel workloads: every rank's share of every split tensor from one plan and one "
+                         "launch set (replicated tensors once); kernel leg only")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
