@@ -139,7 +139,7 @@ class Workload:
             self.source = "procedural byte source (bytes generated into the ring, nothing stored)"
             log(f"{spec.name}: {len(self.sizes)} files, {sum(self.sizes) / 1e9:.2f} GB from the procedural source (not stored)")
         self.fd_arr = (ctypes.c_int * max(len(self.fds), 1))(*self.fds)
-        self.names, self.reqs = [], []
+        self.names, self.reqs, self.marshalled = [], [], None
         for f in spec.files:
             for t in f.tensors:
                 # --all-ranks: one request per (tensor, rank) for the split tensors, replicated tensors once
@@ -161,7 +161,9 @@ class Workload:
         return [self.B.Header(h, n) for h, n in zip(self.model.headers, self.sizes)]
 
     def plan(self, bases, group_bytes, min_gap=None, min_seg=None):
-        p = self.B.Plan(self.headers(), bases, self.names, self.reqs, self.spec.rank, self.spec.world)
+        if self.marshalled is None:
+            self.marshalled = self.B.Requests(self.names, self.reqs)     # the request set is the same for every step
+        p = self.B.Plan(self.headers(), bases, self.marshalled, None, self.spec.rank, self.spec.world)
         p.set_groups(group_bytes, min_gap, min_seg)
         return p
 
@@ -265,8 +267,39 @@ def run_config(spec, args, freed_before, micro=False):
                 "source": w.source,
             }
             log(spec.name, "e2e", res["end_to_end"])
-            stager.close()
             plan.close()
+            if tp and not args.no_streamed:
+                # the same load streamed through a ring of device slots (what a checkpoint larger than device memory
+                # needs), in the three stagings: whole groups as the files hold them, sparse, sparse + compacted
+                buf = None
+                slots = [device.device_bytes(args.stream_slot_bytes, dev) for _ in range(args.stream_slots)]
+                torch.cuda.synchronize()
+                res["end_to_end_streamed"] = []
+                for label, gap, seg in (("whole groups (first to last needed byte of every group)", None, None),
+                                        (f"sparse (gaps > {args.min_gap} B skipped)", args.min_gap, None),
+                                        (f"sparse + compacted (row segments >= {args.min_segment} B)", args.min_gap, args.min_segment)):
+                    sp_ = w.plan([0] * len(w.sizes), args.stream_slot_bytes, gap, seg)
+                    ws2 = device.device_bytes(sp_.workspace_bytes(), dev)
+
+                    def streamed(flags):
+                        t = time.perf_counter()
+                        s = stager.stage_streamed(sp_, read_fn, ctx, [x.data_ptr() for x in slots], args.stream_slot_bytes, ptrs,
+                                                  ws2.data_ptr(), ws2.numel(), flags)
+                        return time.perf_counter() - t, s
+                    t_s, s_s = streamed(0)
+                    t_h, _ = streamed(B.FST_STAGE_NO_KERNELS | B.FST_STAGE_NO_READ)
+                    res["end_to_end_streamed"].append({
+                        "staging": label, "device_slots": f"{args.stream_slots}x{args.stream_slot_bytes >> 30}GiB",
+                        "groups": sp_.group_count(), "staged_gb": round(s_s["staged_bytes"] / 1e9, 3),
+                        "staged_over_bytes_read": round(s_s["staged_bytes"] / rd, 3),
+                        "end_to_end_s": round(t_s, 4), "pure_h2d_s": round(t_h, 4), "end_to_end_over_pure_h2d": round(t_s / t_h, 3),
+                        "runs": "one each"})
+                    log(spec.name, "streamed", res["end_to_end_streamed"][-1])
+                    sp_.close()
+                    del ws2
+                del slots
+                buf = None
+            stager.close()
             if e2e_packed or not resident:
                 buf = None                   # the kernel leg holds its own copy of the raw bytes
             del ws
@@ -546,6 +579,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--no-streamed", action="store_true", help="skip the streamed end-to-end variants of the tensor-parallel configurations")
+    ap.add_argument("--stream-slots", type=int, default=3)
+    ap.add_argument("--stream-slot-bytes", type=int, default=4 << 30)
     ap.add_argument("--all-ranks", action="store_true",
                     help="tensor-parallel workloads: every rank's share of every split tensor from one plan and one "
                          "launch set (replicated tensors once); kernel leg only")

@@ -225,21 +225,33 @@ class Header:
 Request = Tuple
 
 
+class Requests:
+    """Names and requests marshalled once into the C arrays fst_plan_create takes: a caller that plans the same
+    request set again (every step of a benchmark, every reload of a model) passes this instead of the lists."""
+
+    def __init__(self, names: Sequence[str], requests: Sequence[Request]):
+        n = len(names)
+        self.names = list(names)
+        self.n = n
+        self.name_array = (c_char_p * max(n, 1))(*[s.encode("utf-8") for s in names])
+        self.request_array = (fst_request * max(n, 1))()
+        for i, r in enumerate(requests):
+            self.request_array[i] = fst_request(fst_dtype(r[0]), r[1], r[2], r[3] if len(r) > 3 else -1)
+
+
 class Plan:
     """Owner of one fst_plan."""
 
-    def __init__(self, headers: Sequence[Header], raw_base: Sequence[int], names: Sequence[str],
-                 requests: Sequence[Request], rank: int = 0, world: int = 1):
-        n_files, n = len(headers), len(names)
+    def __init__(self, headers: Sequence[Header], raw_base: Sequence[int], names, requests: Optional[Sequence[Request]] = None,
+                 rank: int = 0, world: int = 1):
+        """names: a sequence of tensor names with `requests` beside it, or a Requests object holding both."""
+        m = names if isinstance(names, Requests) else Requests(names, requests)
+        n_files = len(headers)
         hs = (c_void_p * n_files)(*[h.handle for h in headers])
         rb = (c_uint64 * n_files)(*raw_base)
-        nm = (c_char_p * max(n, 1))(*[s.encode("utf-8") for s in names])
-        rq = (fst_request * max(n, 1))()
-        for i, r in enumerate(requests):
-            rq[i] = fst_request(fst_dtype(r[0]), r[1], r[2], r[3] if len(r) > 3 else -1)
         self._p = c_void_p()
-        _check(lib().fst_plan_create(hs, rb, n_files, nm, rq, n, rank, world, byref(self._p)))
-        self.names = list(names)
+        _check(lib().fst_plan_create(hs, rb, n_files, m.name_array, m.request_array, m.n, rank, world, byref(self._p)))
+        self.names = m.names
 
     @classmethod
     def uniform(cls, headers: Sequence[Header], raw_base: Sequence[int], names: Sequence[str],

@@ -487,23 +487,26 @@ int plan_impl(const fst_header *const *hdrs, const uint64_t *raw_base, size_t n_
         p->raw_base.push_back(raw_base[f]);
         p->file_size.push_back(hdrs[f]->file_size);
     }
-    // a tensor name must be unique over the whole file set
+    // one index over the whole file set (a tensor name must be unique over it): name -> (file, tensor)
+    size_t n_tensors = 0;
+    for (size_t f = 0; f < n_files; ++f) n_tensors += hdrs[f]->tensors.size();
+    std::unordered_map<std::string, std::pair<uint32_t, uint32_t>> where;
+    where.reserve(n_tensors * 2);
     for (size_t f = 0; f < n_files; ++f)
-        for (const Tensor &t : hdrs[f]->tensors)
-            for (size_t g = 0; g < f; ++g)
-                if (hdrs[g]->index.count(t.name))
-                    return fail(FST_E_DUP_NAME, "tensor %s is in file %zu and in file %zu", t.name.c_str(), g, f);
+        for (size_t k = 0; k < hdrs[f]->tensors.size(); ++k) {
+            const Tensor &t = hdrs[f]->tensors[k];
+            auto ins = where.emplace(t.name, std::make_pair(uint32_t(f), uint32_t(k)));
+            if (!ins.second)
+                return fail(FST_E_DUP_NAME, "tensor %s is in file %u and in file %zu", t.name.c_str(), ins.first->second.first, f);
+        }
 
     p->outputs.resize(n_names);
     for (size_t i = 0; i < n_names; ++i) {
         if (!names[i]) return fail(FST_E_ARG, "names[%zu] is NULL", i);
-        const Tensor *t = nullptr;
-        size_t file = 0;
-        for (size_t f = 0; f < n_files && !t; ++f) {
-            auto it = hdrs[f]->index.find(names[i]);
-            if (it != hdrs[f]->index.end()) { t = &hdrs[f]->tensors[it->second]; file = f; }
-        }
-        if (!t) return fail(FST_E_NOT_FOUND, "tensor %s is in none of the %zu files", names[i], n_files);
+        auto hit = where.find(names[i]);
+        if (hit == where.end()) return fail(FST_E_NOT_FOUND, "tensor %s is in none of the %zu files", names[i], n_files);
+        const size_t file = hit->second.first;
+        const Tensor *t = &hdrs[file]->tensors[hit->second.second];
         const fst_request &rq = reqs[i];
         const int32_t dd = rq.dst_dtype == FST_KEEP ? t->dtype : rq.dst_dtype;
         if (dd < 0 || dd >= FST_DTYPE_COUNT) return fail(FST_E_DTYPE, "%s: unknown target dtype %d", names[i], rq.dst_dtype);
