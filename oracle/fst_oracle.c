@@ -646,12 +646,45 @@ uint16_t orc_f64_to_bf16(uint64_t x) { return f64_to_16bit(x, 7, 127); }
 uint64_t orc_f16_to_f64(uint16_t h) { return orc_f32_to_f64(orc_f16_to_f32(h)); }
 uint64_t orc_bf16_to_f64(uint16_t b) { return orc_f32_to_f64(orc_bf16_to_f32(b)); }
 
-static int is_float_dtype(int d) { return d == ORC_F64 || d == ORC_F32 || d == ORC_F16 || d == ORC_BF16; }
+/* An 8-bit float with `mb` stored mantissa bits (7 - mb exponent bits) and exponent bias `bias` ->
+ * binary32: always exact.  Two layouts exist (Section VI names the 8-bit types; their definition is
+ * the one of the FP8 formats the paper cites there):
+ *   E5M2 (mb 2, bias 15) follows IEEE 754: exponent field all ones = infinity (mantissa 0) or NaN;
+ *   E4M3 (mb 3, bias 7) has no infinity: exponent field all ones holds ordinary values (up to
+ *   1.75 * 2^8 = 448), except that mantissa all ones there is the NaN.
+ * NaN by the rule above: sign kept, the mantissa field moved to the leading mantissa bits, quiet bit set. */
+static uint32_t f8_to_f32(uint8_t b, int mb, int bias, int ieee_specials)
+{
+    uint32_t s = ((uint32_t)b & 0x80u) << 24;
+    uint32_t emax = (1u << (7 - mb)) - 1u, mmax = (1u << mb) - 1u;
+    uint32_t e = ((uint32_t)b >> mb) & emax;
+    uint32_t m = (uint32_t)b & mmax;
+    if (e == emax && (ieee_specials ? m != 0 : m == mmax))
+        return s | 0x7F800000u | (m << (23 - mb)) | 0x00400000u;  /* NaN */
+    if (e == emax && ieee_specials) return s | 0x7F800000u;       /* infinity */
+    if (e == 0) {
+        if (m == 0) return s;                                     /* +-0 */
+        /* subnormal: value = m * 2^(1 - bias - mb); normalize so that the leading 1 becomes implicit */
+        int k = mb - 1;
+        while (!((m >> k) & 1u)) k--;
+        return s | ((uint32_t)(127 + 1 - bias - mb + k) << 23) | ((m << (23 - k)) & 0x7FFFFFu);
+    }
+    return s | ((e + 127u - (uint32_t)bias) << 23) | (m << (23 - mb));
+}
 
-/* Conversions that exist: among F64, F32, F16 and BF16. */
+uint32_t orc_f8e5m2_to_f32(uint8_t b) { return f8_to_f32(b, 2, 15, 1); }
+uint32_t orc_f8e4m3_to_f32(uint8_t b) { return f8_to_f32(b, 3, 7, 0); }
+
+static int is_float_dtype(int d) { return d == ORC_F64 || d == ORC_F32 || d == ORC_F16 || d == ORC_BF16; }
+static int is_f8_dtype(int d) { return d == ORC_F8_E5M2 || d == ORC_F8_E4M3; }
+
+/* Conversions that exist: among F64, F32, F16 and BF16, and the widenings of the two 8-bit floats to
+ * F16, BF16 and F32 (every 8-bit value is exact in each of them). */
 static int can_convert(int sd, int dd)
 {
-    return sd == dd || (is_float_dtype(sd) && is_float_dtype(dd));
+    if (sd == dd) return 1;
+    if (is_f8_dtype(sd)) return dd == ORC_F16 || dd == ORC_BF16 || dd == ORC_F32;
+    return is_float_dtype(sd) && is_float_dtype(dd);
 }
 
 static uint64_t load_le(const uint8_t *p, uint64_t es)
@@ -676,6 +709,8 @@ static uint64_t convert(uint64_t v, int sd, int dd)
         return sd == ORC_F32 ? orc_f32_to_f64((uint32_t)v) : sd == ORC_F16 ? orc_f16_to_f64((uint16_t)v) : orc_bf16_to_f64((uint16_t)v);
     uint32_t f;
     if (sd == ORC_F32) f = (uint32_t)v;
+    else if (sd == ORC_F8_E5M2) f = orc_f8e5m2_to_f32((uint8_t)v);
+    else if (sd == ORC_F8_E4M3) f = orc_f8e4m3_to_f32((uint8_t)v);
     else if (sd == ORC_F16) f = orc_f16_to_f32((uint16_t)v);
     else f = orc_bf16_to_f32((uint16_t)v);
     if (dd == ORC_F32) return f;

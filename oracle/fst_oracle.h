@@ -94,6 +94,8 @@ uint16_t orc_f64_to_f16(uint64_t x);      /* one rounding from 53 bits, not via 
 uint16_t orc_f64_to_bf16(uint64_t x);
 uint64_t orc_f16_to_f64(uint16_t h);      /* exact */
 uint64_t orc_bf16_to_f64(uint16_t b);
+uint32_t orc_f8e5m2_to_f32(uint8_t b);      /* exact; E5M2 keeps IEEE infinities and NaNs */
+uint32_t orc_f8e4m3_to_f32(uint8_t b);      /* exact; E4M3 has no infinity, S.1111.111 is its NaN */
 /* n elements of src_dtype at src -> dst_dtype at dst. */
 int orc_cast_array(const uint8_t *src, uint64_t n, int src_dtype, int dst_dtype, uint8_t *dst);
 

@@ -81,7 +81,9 @@ def lib() -> ctypes.CDLL:
                          ("orc_f64_to_f16", ctypes.c_uint64, ctypes.c_uint16),
                          ("orc_f64_to_bf16", ctypes.c_uint64, ctypes.c_uint16),
                          ("orc_f16_to_f64", ctypes.c_uint16, ctypes.c_uint64),
-                         ("orc_bf16_to_f64", ctypes.c_uint16, ctypes.c_uint64)]:
+                         ("orc_bf16_to_f64", ctypes.c_uint16, ctypes.c_uint64),
+                         ("orc_f8e5m2_to_f32", ctypes.c_uint8, ctypes.c_uint32),
+                         ("orc_f8e4m3_to_f32", ctypes.c_uint8, ctypes.c_uint32)]:
             getattr(L, fn).argtypes = [a]
             getattr(L, fn).restype = r
         L.orc_cast_array.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,

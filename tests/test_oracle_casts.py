@@ -243,7 +243,8 @@ def test_identity_and_unsupported():
     for dt in ("BOOL", "U8", "I8", "F8_E5M2", "F8_E4M3"):
         assert np.array_equal(orc.cast_array(x, dt, dt), x)
     assert np.array_equal(orc.cast_array(ALL16, "F16", "F16"), ALL16)     # NaN payloads untouched
-    for s, d in (("I16", "F16"), ("U16", "BF16"), ("F64", "I64"), ("U8", "BOOL"), ("F8_E5M2", "F16"), ("I64", "F64")):
+    for s, d in (("I16", "F16"), ("U16", "BF16"), ("F64", "I64"), ("U8", "BOOL"), ("F8_E5M2", "F64"), ("F8_E4M3", "F8_E5M2"),
+                 ("F16", "F8_E4M3"), ("F32", "F8_E5M2"), ("I64", "F64")):
         with pytest.raises(orc.OracleError) as e:
             orc.cast_array(np.zeros(8, np.uint8), s, d)
         assert e.value.kind == "CAST"
@@ -401,3 +402,103 @@ def test_f64_16bit_constants_and_nan():
     n = orc.cast_array(d, "F64", "BF16")
     assert np.all((n & 0x7FC0) == 0x7FC0) and np.array_equal(n >> 15, (d >> np.uint64(63)).astype(np.uint16))
     assert np.array_equal(n & 0x3F, ((d >> np.uint64(45)) & np.uint64(0x3F)).astype(np.uint16))
+
+
+# ---------------------------------------------------------------- 8-bit floats -> F16, BF16, F32
+# The two 8-bit formats (paper Section VI; layouts from the FP8 formats reference cited there): E5M2 =
+# 1-5-2, bias 15, IEEE infinities and NaNs; E4M3 = 1-4-3, bias 7, no infinity, S.1111.111 is the NaN.
+# All 256 inputs of each.  Independent references: torch's CPU float8 types; the value formula of the
+# format evaluated on exact rationals; constants of the formats typed here; E5M2 = the upper byte of a
+# binary16.
+
+ALL8 = np.arange(256, dtype=np.uint8)
+_F8 = {"F8_E5M2": (2, 15, torch.float8_e5m2), "F8_E4M3": (3, 7, torch.float8_e4m3fn)}
+
+
+def _f8_is_nan(fmt):
+    if fmt == "F8_E5M2":
+        return ((ALL8 & 0x7C) == 0x7C) & ((ALL8 & 0x03) != 0)
+    return (ALL8 & 0x7F) == 0x7F
+
+
+@pytest.mark.parametrize("fmt", ["F8_E5M2", "F8_E4M3"])
+def test_f8_widenings_exhaustive_vs_torch(fmt):
+    nan = _f8_is_nan(fmt)
+    t8 = torch.from_numpy(ALL8.copy()).view(_F8[fmt][2])
+    for dst, tdt, view, npdt in (("F32", torch.float32, torch.int32, np.uint32), ("F16", torch.float16, torch.int16, np.uint16),
+                                 ("BF16", torch.bfloat16, torch.int16, np.uint16)):
+        got = orc.cast_array(ALL8, fmt, dst)
+        ref = t8.to(tdt).view(view).numpy().view(npdt)
+        assert np.array_equal(got[~nan], ref[~nan]), (fmt, dst)
+        # the NaNs: NaN in the target, sign kept, quiet
+        f = torch.from_numpy(got[nan].view(np.int32 if npdt is np.uint32 else np.int16)).view(tdt)
+        assert bool(torch.isnan(f).all())
+        top = got.dtype.itemsize * 8 - 1
+        assert np.array_equal(got[nan] >> top, (ALL8[nan] >> 7).astype(got.dtype))
+
+
+@pytest.mark.parametrize("fmt", ["F8_E5M2", "F8_E4M3"])
+def test_f8_to_f32_vs_the_value_formula_on_rationals(fmt):
+    from fractions import Fraction
+    mb, bias, _ = _F8[fmt]
+    nan = _f8_is_nan(fmt)
+    got = orc.cast_array(ALL8, fmt, "F32").view(np.float32)
+    emax = (1 << (7 - mb)) - 1
+    for b in range(256):
+        if nan[b]:
+            continue
+        s, e, m = b >> 7, (b >> mb) & emax, b & ((1 << mb) - 1)
+        if fmt == "F8_E5M2" and e == emax:
+            assert np.isinf(got[b]) and (got[b] < 0) == bool(s)
+            continue
+        if e == 0:
+            v = Fraction(m, 1 << mb) * Fraction(2) ** (1 - bias)
+        else:
+            v = (1 + Fraction(m, 1 << mb)) * Fraction(2) ** (e - bias)
+        assert Fraction(float(got[b])) == (-v if s else v), (fmt, b)
+        assert np.signbit(got[b]) == bool(s)                     # -0 keeps its sign
+
+
+def test_f8_constants():
+    f32 = lambda fmt, b: float(orc.cast_array(np.array([b], np.uint8), fmt, "F32").view(np.float32)[0])
+    bits = lambda fmt, b, dst: int(orc.cast_array(np.array([b], np.uint8), fmt, dst)[0])
+    # E4M3: largest 448 = S.1111.110, smallest normal 2^-6, smallest subnormal 2^-9, no infinity
+    assert f32("F8_E4M3", 0x7E) == 448.0 and f32("F8_E4M3", 0xFE) == -448.0
+    assert f32("F8_E4M3", 0x78) == 256.0                        # exponent field all ones is an ordinary binade
+    assert f32("F8_E4M3", 0x08) == 2.0 ** -6 and f32("F8_E4M3", 0x01) == 2.0 ** -9 and f32("F8_E4M3", 0x07) == 7 * 2.0 ** -9
+    assert f32("F8_E4M3", 0x38) == 1.0 and f32("F8_E4M3", 0xC2) == -2.5 and f32("F8_E4M3", 0x39) == 1.125
+    # E5M2: largest 57344 = S.11110.11, smallest normal 2^-14, smallest subnormal 2^-16, infinity S.11111.00
+    assert f32("F8_E5M2", 0x7B) == 57344.0 and f32("F8_E5M2", 0x04) == 2.0 ** -14 and f32("F8_E5M2", 0x01) == 2.0 ** -16
+    assert f32("F8_E5M2", 0x3C) == 1.0 and f32("F8_E5M2", 0xC1) == -2.5 and f32("F8_E5M2", 0x3D) == 1.25
+    assert bits("F8_E5M2", 0x7C, "F32") == 0x7F800000 and bits("F8_E5M2", 0xFC, "F16") == 0xFC00
+    assert bits("F8_E5M2", 0xFC, "BF16") == 0xFF80
+    # bit patterns typed by hand
+    assert bits("F8_E4M3", 0x38, "F16") == 0x3C00 and bits("F8_E4M3", 0x38, "BF16") == 0x3F80
+    assert bits("F8_E4M3", 0x01, "F16") == 0x1800 and bits("F8_E4M3", 0x01, "BF16") == 0x3B00       # 2^-9
+    assert bits("F8_E4M3", 0x7E, "F16") == 0x5F00 and bits("F8_E4M3", 0x7E, "BF16") == 0x43E0       # 448
+    assert bits("F8_E5M2", 0x01, "F16") == 0x0100 and bits("F8_E5M2", 0x01, "BF16") == 0x3780       # 2^-16: subnormal in F16
+    assert bits("F8_E5M2", 0x80, "F32") == 0x80000000 and bits("F8_E4M3", 0x80, "F16") == 0x8000    # -0
+    # NaN rule: sign kept, mantissa field in the leading mantissa bits, quiet bit set
+    assert bits("F8_E5M2", 0x7D, "F32") == 0x7FE00000 and bits("F8_E5M2", 0xFE, "F32") == 0xFFC00000
+    assert bits("F8_E5M2", 0x7F, "F16") == 0x7F00 and bits("F8_E5M2", 0x7D, "BF16") == 0x7FE0
+    assert bits("F8_E4M3", 0x7F, "F32") == 0x7FF00000 and bits("F8_E4M3", 0xFF, "F16") == 0xFF80
+    assert bits("F8_E4M3", 0x7F, "BF16") == 0x7FF0
+
+
+def test_f8_e5m2_is_the_upper_byte_of_binary16():
+    got = orc.cast_array(ALL8, "F8_E5M2", "F16")
+    nan = _f8_is_nan("F8_E5M2")
+    assert np.array_equal(got[~nan], ALL8[~nan].astype(np.uint16) << 8)
+    assert np.array_equal(orc.cast_array(ALL8, "F8_E5M2", "F32"),
+                          orc.cast_array((ALL8.astype(np.uint16) << 8), "F16", "F32"))
+
+
+@pytest.mark.parametrize("fmt", ["F8_E5M2", "F8_E4M3"])
+def test_f8_widenings_agree_with_each_other_and_keep_order(fmt):
+    f32 = orc.cast_array(ALL8, fmt, "F32")
+    assert np.array_equal(orc.cast_array(orc.cast_array(ALL8, fmt, "F16"), "F16", "F32"), f32)
+    assert np.array_equal(orc.cast_array(orc.cast_array(ALL8, fmt, "BF16"), "BF16", "F32"), f32)
+    top = 0x7C if fmt == "F8_E5M2" else 0x7E                     # largest finite pattern
+    v = f32[:top + 1].view(np.float32)
+    assert np.all(np.diff(v) > 0)                               # positive patterns ascend strictly
+    assert np.array_equal(f32[128:], f32[:128] | np.uint32(0x80000000))
