@@ -454,6 +454,12 @@ def micro_cases():
         ("4096 tensors of 8 KiB, copy", specs.micro_small_tensors(), None),
         ("4096 tensors of 8 KiB, BF16 -> F32", specs.micro_small_tensors(dst="F32"), None),
         ("one tensor of 32 MiB, copy (the same bytes as 4096 x 8 KiB in one piece)", specs.micro_small_tensors(1, 1 << 24), None),
+        ("1 Gi elements of BF16 -> F32 (one byte read for two written)", specs.micro_one_tensor("BF16", 1 << 30, "F32"), None),
+        ("1 Gi elements of F32 -> BF16 (two bytes read for one written)", specs.micro_one_tensor("F32", 1 << 30, "BF16"), None),
+        ("2 Gi elements of 8-bit E4M3 -> BF16", specs.micro_one_tensor("F8_E4M3", 1 << 31, "BF16"), None),
+        ("2 Gi elements of 8-bit E4M3 -> F32", specs.micro_one_tensor("F8_E4M3", 1 << 31, "F32"), None),
+        ("2 Gi elements of 8-bit E5M2 -> F16", specs.micro_one_tensor("F8_E5M2", 1 << 31, "F16"), None),
+        ("2 Gi elements of 8-bit E5M2 -> BF16", specs.micro_one_tensor("F8_E5M2", 1 << 31, "BF16"), None),
     ]
 
 

@@ -121,8 +121,9 @@ void fst_header_free(fst_header *h);
  * A request asks for one named tensor as one rank sees it:
  *   dst_dtype  FST_KEEP, or a floating-point type other than the stored one: any pair among
  *              F64, F32, F16 and BF16 (conversion in the same pass as the copy, Section III-B;
- *              one rounding, to nearest even, also from F64 to a 16-bit type).  Any other pair
- *              with differing types: FST_E_CAST.
+ *              one rounding, to nearest even, also from F64 to a 16-bit type); or F16, BF16 or F32
+ *              for a tensor stored as F8_E5M2 or F8_E4M3 (the 8-bit floats of Section VI; exact).
+ *              Any other pair with differing types: FST_E_CAST.
  *   shard_dim  -1 = whole tensor; d >= 0 = the rank's equal share of dimension d (Section III-B).
  *              Column-wise split of an input projection = dim 0 of the stored [out, in] matrix,
  *              row-wise split of an output projection = dim 1 (Section II-A).

@@ -37,7 +37,7 @@ struct fst_header {
 namespace fst {
 
 // How a descriptor's rows are moved.  The vector path moves whole chunks (16 bytes when nothing
-// is converted, 8 elements otherwise, 4 when binary64 is involved) of rows that are a whole number
+// is converted, 2 to 8 elements otherwise: conv_chunk_elems) of rows that are a whole number
 // of chunks.  The spliced path serves rows that are not, but are at least one chunk long: its
 // chunks are cut from the output stream, so a chunk may take its first units from the end of one
 // row and the rest from the start of the next.  The gather path serves rows shorter than a chunk:
@@ -47,10 +47,10 @@ namespace fst {
 enum Path : uint32_t { PATH_VEC = 0, PATH_ELEM = 1, PATH_SPLICE = 2, PATH_GATHER = 3, PATH_COUNT = 4 };
 
 // Conversion kinds (Section III-B).  COPY moves bytes and ignores the element type.  H = binary16,
-// B = bfloat16, F = binary32, D = binary64.
+// B = bfloat16, F = binary32, D = binary64; E5 and E4 = the 8-bit floats E5M2 and E4M3 (widened only).
 enum Conv : uint32_t {
     CONV_COPY = 0, CONV_H2B, CONV_B2H, CONV_H2F, CONV_B2F, CONV_F2H, CONV_F2B, CONV_D2F, CONV_F2D,
-    CONV_D2H, CONV_D2B, CONV_H2D, CONV_B2D, CONV_COUNT
+    CONV_D2H, CONV_D2B, CONV_H2D, CONV_B2D, CONV_E5H, CONV_E5B, CONV_E5F, CONV_E4H, CONV_E4B, CONV_E4F, CONV_COUNT
 };
 
 // One unit of kernel work, as uploaded to the device (64 bytes).
@@ -218,7 +218,7 @@ constexpr uint64_t SPLICE_PIECE_MAX_UNITS = (1ull << 31) - 64;
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
 uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)
 uint32_t conv_dst_bytes(uint32_t conv);
-uint32_t conv_chunk_elems(uint32_t conv);                     // 16 (bytes) for COPY, 4 with binary64, 8 otherwise
+uint32_t conv_chunk_elems(uint32_t conv);                     // elements per chunk; 16 (bytes) for COPY
 // Bytes of output a lane stores at once: 16, or 8 for binary64 -> 16-bit (4 elements of 2 bytes).
 // A piece's first output byte must be a multiple of it (16-byte aligned where the chunk is longer).
 inline uint32_t conv_store_align(uint32_t conv) { return conv == CONV_D2H || conv == CONV_D2B ? 8 : 16; }

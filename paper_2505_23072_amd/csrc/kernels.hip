@@ -6,9 +6,9 @@
 // consecutive tiles of its launch, one per wavefront (a tile is 64 chunks); the piece a tile
 // belongs to is found through a hint table (one entry per HINT_SPAN tiles) with scalar loads,
 // since it only depends on the workgroup and wavefront index.  In the vector, spliced and gather
-// paths a lane moves one chunk: 16 source bytes when nothing is converted, 8 elements otherwise (4
-// when binary64 is involved), written with full-width stores to an aligned destination.  Latency
-// is covered by occupancy (two workgroups = 32 wavefronts per CU), not by several loads per lane.
+// paths a lane moves one chunk: 16 source bytes when nothing is converted, else 2 to 8 elements
+// (see ConvTraits), written with full-width stores to an aligned destination.  Latency is covered
+// by occupancy (two workgroups = 32 wavefronts per CU), not by several loads per lane.
 //
 // The source may start at any byte.  Sources that are a multiple of 4 are read with 4-byte
 // aligned 16-byte loads.  Others read the enclosing aligned dwords (one more than the chunk
@@ -49,6 +49,8 @@ __device__ __forceinline__ void gstore16(void *p, u32x4 v)
 }
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
 __device__ __forceinline__ void gstore8(void *p, uint32_t x, uint32_t y)
 {
     u32x2 v;
@@ -57,7 +59,7 @@ __device__ __forceinline__ void gstore8(void *p, uint32_t x, uint32_t y)
     __builtin_nontemporal_store(v, (FST_GLOBAL u32x2 *)(p));
 }
 
-struct Chunk32 { u32x4 lo, hi; };                        // up to 32 source or result bytes
+struct Chunk32 { u32x4 lo, hi; };                        // up to 32 source bytes, up to 16 result bytes (in lo)
 
 __device__ __forceinline__ uint32_t shift_bytes(uint32_t hi, uint32_t lo, uint32_t sh)
 {
@@ -96,10 +98,37 @@ __device__ __forceinline__ u32x4 load8(const uint8_t *src)
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
     const uint32_t sh = uint32_t(a) & 3u;
     const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
-    const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
-    const uint32_t e = sh ? gload4(p + 8) : 0u;
-    r.x = shift_bytes(v.y, v.x, sh);
-    r.y = shift_bytes(e, v.y, sh);
+    // three dwords in one load when the third holds wanted bytes, two otherwise
+    if (sh) {
+        const u32x3 v = *(const FST_GLOBAL u32x3_a4 *)(p);
+        r.x = shift_bytes(v.y, v.x, sh);
+        r.y = shift_bytes(v.z, v.y, sh);
+    } else {
+        const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
+        r.x = v.x;
+        r.y = v.y;
+    }
+    return r;
+}
+
+// 4 bytes (in .x) from any address (BYTE) or from a 4-byte aligned one.
+template <bool BYTE>
+__device__ __forceinline__ u32x4 load4(const uint8_t *src)
+{
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (!BYTE) {
+        r.x = __builtin_nontemporal_load((const FST_GLOBAL uint32_t *)(src));
+        return r;
+    }
+    const uintptr_t a = reinterpret_cast<uintptr_t>(src);
+    const uint32_t sh = uint32_t(a) & 3u;
+    const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
+    if (sh) {                                            // the second dword only if it holds wanted bytes
+        const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
+        r.x = shift_bytes(v.y, v.x, sh);
+    } else {
+        r.x = gload4(p);
+    }
     return r;
 }
 
@@ -108,8 +137,10 @@ __device__ __forceinline__ Chunk32 load32(const uint8_t *src)
 {
     Chunk32 c;
     if (!BYTE) {
-        c.lo = gload16_stream(src);
-        c.hi = gload16_stream(src + 16);
+        // two loads per lane share their cache lines with the neighbouring lanes' loads: a streaming
+        // hint on the first would let go of lines the second still needs (measured: 6 % slower)
+        c.lo = gload16(src);
+        c.hi = gload16(src + 16);
         return c;
     }
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
@@ -233,21 +264,54 @@ __device__ __forceinline__ uint32_t double_to_float_odd(uint64_t x)
     return b;
 }
 
+// 8-bit E5M2 (1-5-2, bias 15, infinities and NaNs as in IEEE 754) -> binary16: the same layout with
+// eight more mantissa bits.
+__device__ __forceinline__ uint32_t e5m2_to_half(uint32_t b)
+{
+    const uint32_t h = b << 8;
+    return ((h & 0x7FFFu) > 0x7C00u) ? (h | 0x0200u) : h;
+}
+
+// 8-bit E4M3 (1-4-3, bias 7; no infinity, the exponent field's last binade holds ordinary values up
+// to 448 and mantissa all ones there is the NaN) -> binary32 (exact).  Subnormals: the 3-bit field m
+// stands for m * 2^-9.
+__device__ __forceinline__ uint32_t e4m3_to_float(uint32_t b)
+{
+    const uint32_t sign = (b & 0x80u) << 24;
+    const uint32_t mag = b & 0x7Fu;
+    uint32_t r = (mag << 20) + 0x3C000000u;                              // normal: rebias 7 -> 127
+    if (mag < 0x08u) r = __float_as_uint(float(mag) * 0x1p-9f);          // zero and subnormals
+    if (mag == 0x7Fu) r = 0x7FF00000u;                                   // NaN: mantissa field leading, quiet
+    return sign | r;
+}
+
 template <uint32_t CONV> struct ConvTraits;
 // SRC / DST: bytes of one chunk before and after; UNITS: units per chunk (bytes when copying).
+// A chunk is what one 16-byte store holds after a widening conversion, and 16 bytes to 8 or 4 after
+// a narrowing one: two 16-byte stores per lane, 32 bytes apart from lane to lane, ran at half to
+// two thirds of the rate of one store per lane (a bare kernel with that access shape reaches 3.2
+// TB/s against 6.2 to 6.5), while two loads per lane cost little.
 template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 16; };
 template <> struct ConvTraits<CONV_H2B> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
 template <> struct ConvTraits<CONV_B2H> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 8; };
-template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 8; };
+template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 4; };
+template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 4; };
 template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
 template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
 template <> struct ConvTraits<CONV_D2F> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 4; };
-template <> struct ConvTraits<CONV_F2D> { static constexpr uint32_t SRC = 16, DST = 32, UNITS = 4; };
+template <> struct ConvTraits<CONV_F2D> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 2; };
 template <> struct ConvTraits<CONV_D2H> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
 template <> struct ConvTraits<CONV_D2B> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
-template <> struct ConvTraits<CONV_H2D> { static constexpr uint32_t SRC = 8, DST = 32, UNITS = 4; };
-template <> struct ConvTraits<CONV_B2D> { static constexpr uint32_t SRC = 8, DST = 32, UNITS = 4; };
+template <> struct ConvTraits<CONV_H2D> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 2; };
+template <> struct ConvTraits<CONV_B2D> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 2; };
+template <> struct ConvTraits<CONV_E5H> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_E5B> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_E5F> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 4; };
+template <> struct ConvTraits<CONV_E4H> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_E4B> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
+template <> struct ConvTraits<CONV_E4F> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 4; };
+template <uint32_t CONV> constexpr bool from_e5m2 = CONV == CONV_E5H || CONV == CONV_E5B || CONV == CONV_E5F;
+template <uint32_t CONV> constexpr bool from_e4m3 = CONV == CONV_E4H || CONV == CONV_E4B || CONV == CONV_E4F;
 
 template <uint32_t CONV>
 __device__ __forceinline__ uint32_t convert_bits(uint32_t v)
@@ -258,6 +322,12 @@ __device__ __forceinline__ uint32_t convert_bits(uint32_t v)
     if (CONV == CONV_B2F) return bfloat_to_float(v);
     if (CONV == CONV_F2H) return float_to_half(v);
     if (CONV == CONV_F2B) return float_to_bfloat(v);
+    if (CONV == CONV_E5H) return e5m2_to_half(v);                       // every 8-bit value is exact in all three targets
+    if (CONV == CONV_E5F) return half_to_float(e5m2_to_half(v));
+    if (CONV == CONV_E5B) return float_to_bfloat(half_to_float(e5m2_to_half(v)));
+    if (CONV == CONV_E4F) return e4m3_to_float(v);
+    if (CONV == CONV_E4H) return float_to_half(e4m3_to_float(v));
+    if (CONV == CONV_E4B) return float_to_bfloat(e4m3_to_float(v));
     return v;
 }
 
@@ -321,6 +391,68 @@ __device__ __forceinline__ uint32_t narrow_to_half_pair(f32x2 f)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
 }
 
+// Four E5M2 bytes as two pairs of binary16 (the byte becomes the upper byte of the half).
+__device__ __forceinline__ void e5m2_word_to_half_pairs(uint32_t w, uint32_t &p01, uint32_t &p23)
+{
+    p01 = ((w & 0x000000FFu) << 8) | ((w & 0x0000FF00u) << 16);
+    p23 = ((w >> 8) & 0x0000FF00u) | (w & 0xFF000000u);
+}
+// Byte K of four E4M3 bytes (not the NaN) as binary32: the 7 magnitude bits placed over a binary32's
+// low exponent and leading mantissa bits stand for the value times 2^-120, subnormals included
+// (they land on binary32 subnormals), and the multiplication is exact.
+template <uint32_t K>
+__device__ __forceinline__ uint32_t e4m3_byte_to_float(uint32_t w)
+{
+    constexpr uint32_t UP = K == 3 ? 0u : 20u - 8u * K;                 // byte 3 moves down by 4 instead
+    const uint32_t field = (K == 3 ? w >> 4 : w << UP) & 0x07F00000u;
+    const uint32_t sign = (w << (24u - 8u * K)) & 0x80000000u;
+    return __float_as_uint(__uint_as_float(field) * 0x1p120f) | sign;
+}
+// Two binary32 whose low 16 bits are zero -> two bfloat16.
+__device__ __forceinline__ uint32_t upper_halves(uint32_t a, uint32_t b)
+{
+    return (a >> 16) | (b & 0xFFFF0000u);
+}
+
+// Four finite 8-bit floats in a word -> four binary32.
+template <uint32_t CONV>
+__device__ __forceinline__ u32x4 fp8_word_to_floats(uint32_t w)
+{
+    u32x4 r;
+    if (from_e5m2<CONV>) {
+        uint32_t p01, p23;
+        e5m2_word_to_half_pairs(w, p01, p23);
+        const f32x2 a = widen_half_pair(p01), b = widen_half_pair(p23);
+        r.x = __float_as_uint(a.x); r.y = __float_as_uint(a.y); r.z = __float_as_uint(b.x); r.w = __float_as_uint(b.y);
+    } else {
+        r.x = e4m3_byte_to_float<0>(w); r.y = e4m3_byte_to_float<1>(w);
+        r.z = e4m3_byte_to_float<2>(w); r.w = e4m3_byte_to_float<3>(w);
+    }
+    return r;
+}
+// Four finite 8-bit floats in a word -> four binary16 or bfloat16 in two words.
+template <uint32_t CONV>
+__device__ __forceinline__ u32x2 fp8_word_to_16bit(uint32_t w)
+{
+    u32x2 r;
+    if (CONV == CONV_E5H) {
+        uint32_t p01, p23;
+        e5m2_word_to_half_pairs(w, p01, p23);
+        r.x = p01;
+        r.y = p23;
+        return r;
+    }
+    const u32x4 f = fp8_word_to_floats<CONV>(w);
+    if (CONV == CONV_E5B || CONV == CONV_E4B) {
+        r.x = upper_halves(f.x, f.y);
+        r.y = upper_halves(f.z, f.w);
+    } else {
+        r.x = narrow_to_half_pair(float_pair(f.x, f.y));
+        r.y = narrow_to_half_pair(float_pair(f.z, f.w));
+    }
+    return r;
+}
+
 // True when some element of the chunk has an all-ones exponent field.  Adding the field's lowest
 // bit to the masked field carries into the bit above it exactly when the field is all ones; for
 // two 16-bit elements in a word the lower carry stops at bit 15, below the upper element.
@@ -334,11 +466,18 @@ __device__ __forceinline__ bool chunk_has_inf_or_nan(const Chunk32 &in)
                              ((in.hi.w & MASK) + LOW);
         return (acc & 0x80000000u) != 0;
     }
+    if (from_e5m2<CONV> || from_e4m3<CONV>) {
+        // eight bytes in two words (four in one, the other word zero, for binary32 results); E5M2: exponent field all ones; E4M3: the one NaN pattern (its
+        // last binade is ordinary).  The carry of a byte stops at the byte's own top bit.
+        constexpr uint32_t M8 = from_e5m2<CONV> ? 0x7C7C7C7Cu : 0x7F7F7F7Fu;
+        constexpr uint32_t L8 = from_e5m2<CONV> ? 0x04040404u : 0x01010101u;
+        return ((((in.lo.x & M8) + L8) | ((in.lo.y & M8) + L8)) & 0x80808080u) != 0;
+    }
     constexpr bool WIDE = CONV == CONV_F2H || CONV == CONV_F2B || CONV == CONV_F2D;
     constexpr bool BF = CONV == CONV_B2H || CONV == CONV_B2D;           // (bfloat16 -> binary32 never gets here)
     constexpr uint32_t MASK = WIDE ? 0x7F800000u : BF ? 0x7F807F80u : 0x7C007C00u;
     constexpr uint32_t LOW = WIDE ? 0x00800000u : BF ? 0x00800080u : 0x04000400u;
-    if (ConvTraits<CONV>::SRC == 8)                                      // four 16-bit elements in two words
+    if (ConvTraits<CONV>::SRC <= 8)                                      // up to four 16-bit or two 32-bit elements in two words (unused ones zero)
         return ((((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW)) & 0x80008000u) != 0;
     uint32_t acc = ((in.lo.x & MASK) + LOW) | ((in.lo.y & MASK) + LOW) | ((in.lo.z & MASK) + LOW) |
                    ((in.lo.w & MASK) + LOW);
@@ -364,11 +503,8 @@ __device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
         o.lo.w = narrow_to_half_pair(widen_bfloat_pair(in.lo.w));
     } else if (CONV == CONV_H2F) {
         const f32x2 a = widen_half_pair(in.lo.x), b = widen_half_pair(in.lo.y);
-        const f32x2 c = widen_half_pair(in.lo.z), d = widen_half_pair(in.lo.w);
         o.lo.x = __float_as_uint(a.x); o.lo.y = __float_as_uint(a.y);
         o.lo.z = __float_as_uint(b.x); o.lo.w = __float_as_uint(b.y);
-        o.hi.x = __float_as_uint(c.x); o.hi.y = __float_as_uint(c.y);
-        o.hi.z = __float_as_uint(d.x); o.hi.w = __float_as_uint(d.y);
     } else if (CONV == CONV_F2H) {
         o.lo.x = narrow_to_half_pair(float_pair(in.lo.x, in.lo.y));
         o.lo.y = narrow_to_half_pair(float_pair(in.lo.z, in.lo.w));
@@ -387,10 +523,7 @@ __device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
     } else if (CONV == CONV_F2D) {
         const uint64_t a = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.x))));
         const uint64_t b = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.y))));
-        const uint64_t c = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.z))));
-        const uint64_t d = uint64_t(__double_as_longlong(double(__uint_as_float(in.lo.w))));
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
-        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     } else if (CONV == CONV_D2H || CONV == CONV_D2B) {
         const uint32_t a = double_to_float_odd(in.lo.x | (uint64_t(in.lo.y) << 32));
         const uint32_t b = double_to_float_odd(in.lo.z | (uint64_t(in.lo.w) << 32));
@@ -405,16 +538,31 @@ __device__ __forceinline__ Chunk32 convert_chunk_finite(const Chunk32 &in)
         }
     } else if (CONV == CONV_H2D || CONV == CONV_B2D) {
         const f32x2 p = CONV == CONV_H2D ? widen_half_pair(in.lo.x) : widen_bfloat_pair(in.lo.x);
-        const f32x2 q = CONV == CONV_H2D ? widen_half_pair(in.lo.y) : widen_bfloat_pair(in.lo.y);
         const uint64_t a = uint64_t(__double_as_longlong(double(p.x))), b = uint64_t(__double_as_longlong(double(p.y)));
-        const uint64_t c = uint64_t(__double_as_longlong(double(q.x))), d = uint64_t(__double_as_longlong(double(q.y)));
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
-        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
+    } else if (CONV == CONV_E5F || CONV == CONV_E4F) {
+        o.lo = fp8_word_to_floats<CONV>(in.lo.x);                       // four bytes in a word -> four binary32
+    } else if (from_e5m2<CONV> || from_e4m3<CONV>) {
+        // eight bytes in two words -> eight 16-bit elements
+        const u32x2 a = fp8_word_to_16bit<CONV>(in.lo.x), b = fp8_word_to_16bit<CONV>(in.lo.y);
+        o.lo.x = a.x; o.lo.y = a.y; o.lo.z = b.x; o.lo.w = b.y;
     }
     return o;
 }
 
-// One chunk: 8 elements (4 with binary64, or 16 raw bytes) in, converted out.
+// The four 8-bit floats of a word converted one by one, whatever they hold.
+template <uint32_t CONV>
+__device__ __forceinline__ u32x4 fp8_word_any(uint32_t w)
+{
+    u32x4 r;
+    r.x = convert_bits<CONV>(w & 0xFFu);
+    r.y = convert_bits<CONV>((w >> 8) & 0xFFu);
+    r.z = convert_bits<CONV>((w >> 16) & 0xFFu);
+    r.w = convert_bits<CONV>(w >> 24);
+    return r;
+}
+
+// One chunk (2 to 8 elements, or 16 raw bytes) in, converted out.
 template <uint32_t CONV>
 __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
 {
@@ -434,10 +582,6 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
         o.lo.y = convert_bits<CONV>(in.lo.x >> 16);
         o.lo.z = convert_bits<CONV>(in.lo.y & 0xFFFFu);
         o.lo.w = convert_bits<CONV>(in.lo.y >> 16);
-        o.hi.x = convert_bits<CONV>(in.lo.z & 0xFFFFu);
-        o.hi.y = convert_bits<CONV>(in.lo.z >> 16);
-        o.hi.z = convert_bits<CONV>(in.lo.w & 0xFFFFu);
-        o.hi.w = convert_bits<CONV>(in.lo.w >> 16);
     } else if (CONV == CONV_D2F) {
         o.lo.x = double_to_float(in.lo.x | (uint64_t(in.lo.y) << 32));
         o.lo.y = double_to_float(in.lo.z | (uint64_t(in.lo.w) << 32));
@@ -445,9 +589,7 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
         o.lo.w = double_to_float(in.hi.z | (uint64_t(in.hi.w) << 32));
     } else if (CONV == CONV_F2D) {
         const uint64_t a = float_to_double(in.lo.x), b = float_to_double(in.lo.y);
-        const uint64_t c = float_to_double(in.lo.z), d = float_to_double(in.lo.w);
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
-        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
     } else if (CONV == CONV_D2H || CONV == CONV_D2B) {
         const uint32_t a = uint32_t(convert_element<CONV>(in.lo.x | (uint64_t(in.lo.y) << 32)));
         const uint32_t b = uint32_t(convert_element<CONV>(in.lo.z | (uint64_t(in.lo.w) << 32)));
@@ -457,9 +599,12 @@ __device__ __forceinline__ Chunk32 convert_chunk(const Chunk32 &in)
         o.lo.y = c | (d << 16);
     } else if (CONV == CONV_H2D || CONV == CONV_B2D) {
         const uint64_t a = convert_element<CONV>(in.lo.x & 0xFFFFu), b = convert_element<CONV>(in.lo.x >> 16);
-        const uint64_t c = convert_element<CONV>(in.lo.y & 0xFFFFu), d = convert_element<CONV>(in.lo.y >> 16);
         o.lo.x = uint32_t(a); o.lo.y = uint32_t(a >> 32); o.lo.z = uint32_t(b); o.lo.w = uint32_t(b >> 32);
-        o.hi.x = uint32_t(c); o.hi.y = uint32_t(c >> 32); o.hi.z = uint32_t(d); o.hi.w = uint32_t(d >> 32);
+    } else if (CONV == CONV_E5F || CONV == CONV_E4F) {
+        o.lo = fp8_word_any<CONV>(in.lo.x);
+    } else if (from_e5m2<CONV> || from_e4m3<CONV>) {
+        const u32x4 a = fp8_word_any<CONV>(in.lo.x), b = fp8_word_any<CONV>(in.lo.y);
+        o.lo.x = a.x | (a.y << 16); o.lo.y = a.z | (a.w << 16); o.lo.z = b.x | (b.y << 16); o.lo.w = b.z | (b.w << 16);
     } else {
         o.lo.x = convert_bits<CONV>(in.lo.x) | (convert_bits<CONV>(in.lo.y) << 16);
         o.lo.y = convert_bits<CONV>(in.lo.z) | (convert_bits<CONV>(in.lo.w) << 16);
@@ -547,7 +692,8 @@ template <uint32_t CS, bool BYTE>
 __device__ __forceinline__ Chunk32 load_chunk(const uint8_t *s)
 {
     Chunk32 v;
-    if (CS == 8) v.lo = load8<BYTE>(s);
+    if (CS == 4) v.lo = load4<BYTE>(s);
+    else if (CS == 8) v.lo = load8<BYTE>(s);
     else if (CS == 16) v.lo = load16<BYTE>(s);
     else v = load32<BYTE>(s);
     return v;
@@ -556,12 +702,9 @@ __device__ __forceinline__ Chunk32 load_chunk(const uint8_t *s)
 template <uint32_t CD>
 __device__ __forceinline__ void store_chunk(uint8_t *t, const Chunk32 &o)
 {
-    if (CD == 8) {
-        gstore8(t, o.lo.x, o.lo.y);
-    } else {
-        gstore16(t, o.lo);
-        if (CD == 32) gstore16(t + 16, o.hi);
-    }
+    static_assert(CD == 8 || CD == 16, "one store per lane");
+    if (CD == 8) gstore8(t, o.lo.x, o.lo.y);
+    else gstore16(t, o.lo);
 }
 
 // One chunk per lane: chunk c of the piece (c < n_units) is read at its row/column offset from
@@ -757,7 +900,8 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_gather(const De
             const uint32_t r = fast_div(u, d.div_m(), d.div_s());
             const uint8_t *p = base + uint64_t(r) * d.src_stride() + uint64_t(u - r * d.units_per_row()) * US;
             const uint64_t e = aligned ? load_unit<US>(p) : load_bytes<US>(p);
-            if (US == 2) chunk_or(v, j / 2, uint32_t(e) << (16 * (j % 2)));
+            if (US == 1) chunk_or(v, j / 4, uint32_t(e) << (8 * (j % 4)));
+            else if (US == 2) chunk_or(v, j / 2, uint32_t(e) << (16 * (j % 2)));
             else if (US == 4) chunk_or(v, j, uint32_t(e));
             else { chunk_or(v, 2 * j, uint32_t(e)); chunk_or(v, 2 * j + 1, uint32_t(e >> 32)); }
         }
@@ -855,6 +999,12 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
     case CONV_D2B: return launch_conv<CONV_D2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
     case CONV_H2D: return launch_conv<CONV_H2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
     case CONV_B2D: return launch_conv<CONV_B2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E5H: return launch_conv<CONV_E5H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E5B: return launch_conv<CONV_E5B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E5F: return launch_conv<CONV_E5F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E4H: return launch_conv<CONV_E4H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E4B: return launch_conv<CONV_E4B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
+    case CONV_E4F: return launch_conv<CONV_E4F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
     default: return fail(FST_E_ARG, "unknown launch class %u", cls);
     }
 }

@@ -79,7 +79,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
             return fail(FST_E_RANGE, "output %u reads bytes [%llu, %llu) but the buffer has %zu", pc->output,
                         (unsigned long long)src_off, (unsigned long long)(src_off + pc->src_span), src_len);
         const uint32_t cls = launch_class(*pc);
-        if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(descs.size()), 0, 0, 0});
+        if (ranges.empty() || ranges.back().cls != cls) ranges.push_back({cls, uint32_t(descs.size()), 0, 0, 0, 0});
         LaunchRange &r = ranges.back();
         DevDesc d{};
         d.src_off = src_off;

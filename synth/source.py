@@ -46,11 +46,15 @@ def lib() -> ctypes.CDLL:
 
 
 def _normal_pool(dtype: str, seed: int) -> np.ndarray:
-    """POOL_PRIME samples of N(0, 0.02) stored as `dtype`, as raw bytes."""
+    """POOL_PRIME samples of N(0, 0.02) stored as `dtype`, as raw bytes (the 8-bit floats: N(0, 1), as weights
+    quantized with a scale that brings them into the format's range would look)."""
     import torch
     g = torch.Generator().manual_seed(seed * 1000003 + 17)
-    x = torch.randn(POOL_PRIME, generator=g, dtype=torch.float32) * 0.02
-    tdt = {"BF16": torch.bfloat16, "F16": torch.float16, "F32": torch.float32, "F64": torch.float64}[dtype]
+    x = torch.randn(POOL_PRIME, generator=g, dtype=torch.float32)
+    tdt = {"BF16": torch.bfloat16, "F16": torch.float16, "F32": torch.float32, "F64": torch.float64,
+           "F8_E5M2": torch.float8_e5m2, "F8_E4M3": torch.float8_e4m3fn}[dtype]
+    if not dtype.startswith("F8_"):
+        x = x * 0.02
     return x.to(tdt).view(torch.uint8).numpy().copy()
 
 

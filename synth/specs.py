@@ -265,6 +265,13 @@ def micro_small_tensors(n: int = 4096, elems: int = 4096, dst: Optional[str] = N
     return ModelSpec(f"{n}-tensors-of-{elems * 2}B" + (f"-to-{dst}" if dst else ""), 73, [FileSpec("a.safetensors", ts, 5)])
 
 
+def micro_one_tensor(dtype: str, elems: int, dst: Optional[str] = None, residue: int = 3) -> ModelSpec:
+    """One vector of `elems` elements of `dtype`, converted to `dst`; the file body starts at `residue` mod 16."""
+    t = TensorSpec("w", dtype, (elems,), dst_dtype=dst)
+    return ModelSpec(f"one-{dtype}-tensor-of-{elems}" + (f"-to-{dst}" if dst else ""), 74,
+                     [FileSpec("a.safetensors", [t], residue)])
+
+
 CONFIGS = {
     "tiny": config1_tiny,
     "llama-7b": config2_llama7b,

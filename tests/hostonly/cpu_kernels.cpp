@@ -61,16 +61,22 @@ ConvInfo conv_info(uint32_t conv)
     case CONV_COPY: return {16, 16, 16, ORC_U8, ORC_U8};
     case CONV_H2B: return {16, 16, 8, ORC_F16, ORC_BF16};
     case CONV_B2H: return {16, 16, 8, ORC_BF16, ORC_F16};
-    case CONV_H2F: return {16, 32, 8, ORC_F16, ORC_F32};
-    case CONV_B2F: return {16, 32, 8, ORC_BF16, ORC_F32};
+    case CONV_H2F: return {8, 16, 4, ORC_F16, ORC_F32};
+    case CONV_B2F: return {8, 16, 4, ORC_BF16, ORC_F32};
     case CONV_F2H: return {32, 16, 8, ORC_F32, ORC_F16};
     case CONV_F2B: return {32, 16, 8, ORC_F32, ORC_BF16};
     case CONV_D2F: return {32, 16, 4, ORC_F64, ORC_F32};
-    case CONV_F2D: return {16, 32, 4, ORC_F32, ORC_F64};
+    case CONV_F2D: return {8, 16, 2, ORC_F32, ORC_F64};
     case CONV_D2H: return {32, 8, 4, ORC_F64, ORC_F16};
     case CONV_D2B: return {32, 8, 4, ORC_F64, ORC_BF16};
-    case CONV_H2D: return {8, 32, 4, ORC_F16, ORC_F64};
-    default: return {8, 32, 4, ORC_BF16, ORC_F64};
+    case CONV_H2D: return {4, 16, 2, ORC_F16, ORC_F64};
+    case CONV_E5H: return {8, 16, 8, ORC_F8_E5M2, ORC_F16};
+    case CONV_E5B: return {8, 16, 8, ORC_F8_E5M2, ORC_BF16};
+    case CONV_E5F: return {4, 16, 4, ORC_F8_E5M2, ORC_F32};
+    case CONV_E4H: return {8, 16, 8, ORC_F8_E4M3, ORC_F16};
+    case CONV_E4B: return {8, 16, 8, ORC_F8_E4M3, ORC_BF16};
+    case CONV_E4F: return {4, 16, 4, ORC_F8_E4M3, ORC_F32};
+    default: return {4, 16, 2, ORC_BF16, ORC_F64};
     }
 }
 

@@ -153,7 +153,8 @@ def test_random_files(seed):
 def test_ragged_rows(residue):
     rng = np.random.default_rng(300 + residue)
     spec = [("a", "BF16", (60, 1096), 8), ("b", "F32", (70, 44), 4), ("c", "I8", (90, 100), 4), ("d", "F16", (129, 72), 8),
-            ("e", "BF16", (6, 50, 21), 5), ("g", "F32", (131, 72), 8), ("h", "F64", (80, 44), 4), ("i", "F64", (129, 40), 8)]
+            ("e", "BF16", (6, 50, 21), 5), ("g", "F32", (131, 72), 8), ("h", "F64", (80, 44), 4), ("i", "F64", (129, 40), 8),
+            ("m", "F8_E4M3", (90, 100), 4), ("n", "F8_E5M2", (129, 72), 8)]
     ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
     ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
     ts.append(("qkv", "BF16", (120, 37), random_bits(rng, "BF16", (120, 37)).tobytes()))
@@ -177,7 +178,8 @@ def test_rows_shorter_than_a_chunk(residue):
     rng = np.random.default_rng(500 + residue)
     spec = [("a", "U8", (700, 24), 8), ("b", "U8", (301, 26), 2), ("c", "I16", (410, 12), 4), ("d", "BF16", (290, 8), 8),
             ("e", "F32", (150, 6), 2), ("f", "F16", (205, 14), 2), ("g", "F64", (90, 6), 2), ("h", "I64", (70, 2), 2),
-            ("i", "BF16", (33, 7, 10), 5), ("j", "F32", (110, 9), 3), ("k", "U8", (200, 30), 2), ("l", "F64", (120, 3), 3)]
+            ("i", "BF16", (33, 7, 10), 5), ("j", "F32", (110, 9), 3), ("k", "U8", (200, 30), 2), ("l", "F64", (120, 3), 3),
+            ("m", "F8_E4M3", (300, 12), 4), ("n", "F8_E5M2", (100, 14), 2)]
     ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
     ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
     blob = writer.write_file(None, ts, None, residue)

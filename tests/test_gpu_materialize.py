@@ -63,7 +63,7 @@ def test_every_source_alignment(residue):
     """Body start at every residue mod 16, with an odd-sized tensor in front to shift the rest by one."""
     rng = np.random.default_rng(residue)
     ts = [("pad", "U8", (residue % 3,), random_bits(rng, "U8", (residue % 3,)).tobytes())]
-    for dt in ("BF16", "F16", "F32", "F64", "I8", "I64"):
+    for dt in ("BF16", "F16", "F32", "F64", "I8", "I64", "F8_E4M3", "F8_E5M2"):
         ts.append((f"w.{dt}", dt, SHAPE, random_bits(rng, dt, SHAPE).tobytes()))
         ts.append((f"v.{dt}", dt, (1031,), random_bits(rng, dt, (1031,)).tobytes()))
     blob = writer.write_file(None, ts, None, residue)
@@ -148,7 +148,8 @@ def test_ragged_rows_of_at_least_one_chunk(residue):
     rng = np.random.default_rng(300 + residue)
     spec = [("a", "BF16", (300, 1096), 8), ("b", "F32", (200, 44), 4), ("c", "I8", (300, 100), 4),
             ("d", "F16", (129, 72), 8), ("e", "BF16", (6, 50, 21), 5), ("f", "BF16", (4099, 1100), 4),
-            ("g", "F32", (1031, 72), 8), ("h", "F64", (300, 44), 4), ("i", "F64", (129, 40), 8)]
+            ("g", "F32", (1031, 72), 8), ("h", "F64", (300, 44), 4), ("i", "F64", (129, 40), 8),
+            ("m", "F8_E4M3", (300, 100), 4), ("n", "F8_E5M2", (129, 72), 8)]
     ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
     ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
     ts.append(("qkv", "BF16", (120, 37), random_bits(rng, "BF16", (120, 37)).tobytes()))
@@ -190,6 +191,25 @@ def test_exhaustive_16bit_conversions_on_device(src, dst):
         assert got[0] == want, f"{src}->{dst} lead {lead}: {first_diff(got[0], want)}"
 
 
+@pytest.mark.parametrize("src", ["F8_E5M2", "F8_E4M3"])
+def test_8bit_float_widenings_on_device(src):
+    """All 256 patterns of an 8-bit float to F16, BF16 and F32: in order (chunks that hold NaNs or infinities
+    take the integer formulation), every finite pattern eight times in a row (chunks without any take the
+    other one), random bytes over several tiles; sources at every offset modulo 4."""
+    rng = np.random.default_rng(8)
+    allbits = np.arange(256, dtype=np.uint8)
+    special = ((allbits & 0x7C) == 0x7C) if src == "F8_E5M2" else ((allbits & 0x7F) == 0x7F)
+    x = np.concatenate([allbits, np.repeat(allbits[~special], 8), rng.integers(0, 256, 70_001, dtype=np.uint8)])
+    for lead in (0, 1, 2, 3):
+        ts = [("lead", "U8", (lead,), bytes(lead)), ("x", src, (len(x),), x.tobytes())]
+        blob = writer.write_file(None, ts, None, 0)
+        dsts = ["F16", "BF16", "F32"]
+        got, _ = materialize_resident([blob], ["x"] * 3, [(d, -1, 1) for d in dsts])
+        for d, g in zip(dsts, got):
+            want = orc.cast_array(x, src, d).tobytes()
+            assert g == want, f"{src}->{d} lead {lead}: {first_diff(g, want)}"
+
+
 @pytest.mark.parametrize("dst", ["BF16", "F16"])
 def test_f32_conversions_on_device(dst):
     rng = np.random.default_rng(5)
@@ -217,7 +237,8 @@ def test_rows_shorter_than_a_chunk(residue):
     # (name, dtype, shape, world): the share along the last dimension is shape[-1] / world elements
     spec = [("a", "U8", (5000, 24), 8), ("b", "U8", (3001, 26), 2), ("c", "I16", (4100, 12), 4), ("d", "BF16", (2900, 8), 8),
             ("e", "F32", (1500, 6), 2), ("f", "F16", (2050, 14), 2), ("g", "F64", (900, 6), 2), ("h", "I64", (700, 2), 2),
-            ("i", "BF16", (33, 7, 10), 5), ("j", "F32", (1100, 9), 3), ("k", "U8", (2000, 30), 2), ("l", "F64", (1200, 3), 3)]
+            ("i", "BF16", (33, 7, 10), 5), ("j", "F32", (1100, 9), 3), ("k", "U8", (2000, 30), 2), ("l", "F64", (1200, 3), 3),
+            ("m", "F8_E4M3", (3000, 12), 4), ("n", "F8_E5M2", (1000, 14), 2)]
     ts = [("lead", "U8", (residue % 3,), bytes(residue % 3))]
     ts += [(n, dt, shape, random_bits(rng, dt, shape).tobytes()) for n, dt, shape, _ in spec]
     blob = writer.write_file(None, ts, None, residue)

@@ -10,10 +10,14 @@ NP = {"U8": np.uint8, "I8": np.int8, "I16": np.int16, "U16": np.uint16, "F16": n
 ES = {k: np.dtype(v).itemsize for k, v in NP.items()}
 FLOATS = ("F32", "F16", "BF16")
 ALL_FLOATS = ("F64", "F32", "F16", "BF16")
+F8S = ("F8_E5M2", "F8_E4M3")
+F8_TARGETS = ("F16", "BF16", "F32")
 
 
 def cast_targets(dtype):
     """The element types a stored dtype can be converted to (other than itself)."""
+    if dtype in F8S:
+        return list(F8_TARGETS)
     return [d for d in ALL_FLOATS if d != dtype] if dtype in ALL_FLOATS else []
 
 
@@ -50,6 +54,8 @@ def random_request(rng, dtype, shape, world):
         dst = "F64" if dtype == "F32" else "F32"
     if dtype in ALL_FLOATS and rng.random() < 0.15:          # drawn last: the older cases keep their requests
         dst = ALL_FLOATS[int(rng.integers(4))]
+    if dtype in F8S and rng.random() < 0.5:
+        dst = F8_TARGETS[int(rng.integers(3))]
     dims = [d for d in range(len(shape)) if shape[d] % world == 0]
     if not dims or rng.random() < 0.25:
         return dst, -1, 1
