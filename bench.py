@@ -139,7 +139,7 @@ class Workload:
             self.source = "procedural byte source (bytes generated into the ring, nothing stored)"
             log(f"{spec.name}: {len(self.sizes)} files, {sum(self.sizes) / 1e9:.2f} GB from the procedural source (not stored)")
         self.fd_arr = (ctypes.c_int * max(len(self.fds), 1))(*self.fds)
-        self.names, self.reqs, self.marshalled = [], [], None
+        self.names, self.reqs, self.marshalled, self._phases = [], [], None, None
         for f in spec.files:
             for t in f.tensors:
                 # --all-ranks: one request per (tensor, rank) for the split tensors, replicated tensors once
@@ -147,6 +147,24 @@ class Workload:
                 for r in ranks:
                     self.names.append(t.name)
                     self.reqs.append((t.dst_dtype, t.shard_dim, t.blocks, r) if r >= 0 else (t.dst_dtype, t.shard_dim, t.blocks))
+
+    def phases(self):
+        """raw_base phase of every file: the one that puts its tensor data on a 256-byte boundary in device memory
+        (default), or 0 = the alignment the bytes have in the file (--file-phase keep)."""
+        if self._phases is None:
+            if getattr(self.args, "file_phase", "aligned") == "keep":
+                self._phases = [0] * len(self.sizes)
+            else:
+                self._phases = [h.aligned_phase() for h in self.headers()]
+        return self._phases
+
+    def bases(self):
+        """Where whole files sit in one resident raw buffer, and its length."""
+        bases, at = [], 0
+        for ph, s in zip(self.phases(), self.sizes):
+            bases.append(at + ph)
+            at += (ph + s + 255) // 256 * 256
+        return bases, max(at, 256)
 
     def read_callback(self):
         if self.from_files:
@@ -186,7 +204,7 @@ def run_config(spec, args, freed_before, micro=False):
     dev = device.require_gpu()
     w = Workload(spec, args)
     try:
-        bases, raw_len = device.file_bases(w.sizes)
+        bases, raw_len = w.bases()
         probe = w.plan(bases, 0)
         out_bytes = probe.write_bytes()
         rd, wr = probe.read_bytes(), probe.write_bytes()
@@ -206,7 +224,7 @@ def run_config(spec, args, freed_before, micro=False):
         e2e_packed = tp
 
         def e2e_plan():
-            return w.plan([0] * len(w.sizes) if e2e_packed else bases, args.group_bytes, e2e_gap, e2e_seg)
+            return w.plan(w.phases() if e2e_packed else bases, args.group_bytes, e2e_gap, e2e_seg)
 
         read_fn, ctx = w.read_callback()
         torch.cuda.synchronize()
@@ -278,7 +296,7 @@ def run_config(spec, args, freed_before, micro=False):
                 for label, gap, seg in (("whole groups (first to last needed byte of every group)", None, None),
                                         (f"sparse (gaps > {args.min_gap} B skipped)", args.min_gap, None),
                                         (f"sparse + compacted (row segments >= {args.min_segment} B)", args.min_gap, args.min_segment)):
-                    sp_ = w.plan([0] * len(w.sizes), args.stream_slot_bytes, gap, seg)
+                    sp_ = w.plan(w.phases(), args.stream_slot_bytes, gap, seg)
                     ws2 = device.device_bytes(sp_.workspace_bytes(), dev)
 
                     def streamed(flags):
@@ -310,7 +328,7 @@ def run_config(spec, args, freed_before, micro=False):
 
         # ---------------- kernel leg: staged bytes resident in HBM
         k_gap = None if resident else args.min_gap
-        k_bases = bases if resident else [0] * len(w.sizes)
+        k_bases = bases if resident else w.phases()
         layout = B.FST_LAYOUT_RESIDENT if resident else B.FST_LAYOUT_PACKED
         plan = w.plan(k_bases, args.group_bytes, k_gap)
         src_len = raw_len if resident else plan.packed_bytes()
@@ -402,12 +420,13 @@ def run_config(spec, args, freed_before, micro=False):
         if per_group:
             nbytes = [g["read_bytes"] + g["write_bytes"] for g in groups]
             dom = int(np.argmax(nbytes))
-            align = len(w.model.headers[groups[dom]["file"]]) % 16
+            residue = lambda f: (len(w.model.headers[f]) + w.phases()[f]) % 16      # of the tensor data in device memory
+            align = residue(groups[dom]["file"])
             if all(r[:3] == (None, -1, 1) for r in w.reqs):
                 kernel = "materialize_vec<COPY, byte-aligned source>" if align % 4 else "materialize_vec<COPY, dword-aligned source>"
             else:
                 kernel = "materialize kernels of the largest file (its conversions and partitions)"
-            launches = [{"file": groups[g]["file"], "source_residue_mod16": len(w.model.headers[groups[g]["file"]]) % 16,
+            launches = [{"file": groups[g]["file"], "source_residue_mod16": residue(groups[g]["file"]),
                          "bytes": nbytes[g], "ms_avg": round(float(spans[:, g].mean()), 4),
                          "gbps": round(nbytes[g] / (spans[:, g].mean() * 1e-3) / 1e9, 1)} for g in range(ng0)]
             dom_ms, dom_min, dom_bytes = float(spans[:, dom].mean()), float(spans[:, dom].min()), nbytes[dom]
@@ -476,7 +495,7 @@ def run_micro(args):
     for title, spec, group_bytes in micro_cases():
         w = Workload(spec, argparse.Namespace(**{**vars(args), "no_files": True}))
         try:
-            bases, raw_len = device.file_bases(w.sizes)
+            bases, raw_len = w.bases()
             plan = w.plan(bases, group_bytes or 0)
             raw = device.device_bytes(raw_len)
             ws = device.device_bytes(plan.workspace_bytes())
@@ -593,6 +612,9 @@ def main() -> int:
                          "launch set (replicated tensors once); kernel leg only")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device-to-device copy (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--file-phase", choices=("aligned", "keep"), default="aligned",
+                    help="where a file's bytes sit in device memory modulo 256: 'aligned' shifts every file so that its tensor "
+                         "data starts on a 256-byte boundary, 'keep' leaves every byte at its file offset's residue")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
     ap.add_argument("--min-gap", type=int, default=1 << 20,
                     help="sparse staging (tensor-parallel configurations): unread file ranges longer than this are not staged")

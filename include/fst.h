@@ -111,6 +111,10 @@ int fst_header_tensor(const fst_header *h, size_t i, fst_tensor_info *out);
 /* Index of the tensor called `name`, or FST_E_NOT_FOUND. */
 int64_t fst_header_find(const fst_header *h, const char *name);
 uint64_t fst_header_body_offset(const fst_header *h);   /* 8 + N */
+/* The raw_base phase (below FST_RAW_ALIGN) that puts the first byte after the header, and with it
+ * every tensor whose offset in the body is a multiple of 4 or 16, on such a boundary in device
+ * memory: -(8 + N) modulo FST_RAW_ALIGN.  See fst_plan_create. */
+uint64_t fst_aligned_phase(const fst_header *h);
 uint64_t fst_header_file_size(const fst_header *h);
 size_t fst_header_metadata_count(const fst_header *h);
 int fst_header_metadata(const fst_header *h, size_t i, const char **key, const char **value);
@@ -143,9 +147,13 @@ typedef struct fst_request {
 
 /*
  * hdrs[f] (host): header of file f.  raw_base[f]: byte offset inside the raw device buffer at
- * which byte 0 of file f lands when files are resident (multiple of FST_RAW_ALIGN, else
- * FST_E_ALIGN); a tensor's bytes then start at raw + raw_base[f] + 8 + N_f + begin, at whatever
- * alignment that gives.  names[i] (host, NUL-terminated UTF-8) with reqs[i]; a name must exist in
+ * which byte 0 of file f lands when files are resident; a tensor's bytes then start at raw +
+ * raw_base[f] + 8 + N_f + begin, at whatever alignment that gives.  Any value is allowed, and
+ * raw_base[f] % FST_RAW_ALIGN is the phase of file f in every layout: file byte x sits at an
+ * address congruent to x + raw_base[f] modulo FST_RAW_ALIGN, staged resident, in a slot or
+ * packed.  A multiple of FST_RAW_ALIGN keeps the alignment the bytes have in the file; a caller
+ * that wants the tensor data itself aligned (the kernels read 4-byte aligned sources with fewer
+ * loads) picks raw_base[f] congruent to -(8 + N_f): fst_aligned_phase(hdr).  names[i] (host, NUL-terminated UTF-8) with reqs[i]; a name must exist in
  * exactly one file (FST_E_NOT_FOUND / FST_E_DUP_NAME).  The plan copies what it needs; hdrs may
  * be freed afterwards.  Output i of the plan belongs to names[i].
  */
@@ -182,8 +190,8 @@ int fst_plan_output(const fst_plan *p, size_t i, fst_output_info *out);
  * Resident layout: byte o of file f is at raw + raw_base[f] + o.
  * Slot layout: the group's staged bytes are alone in a slot.  A group stages one or more extents
  *   (byte ranges of its file); byte o of extent e is at slot + e.slot_offset + (o - e.lo), where
- *   e.slot_offset % FST_RAW_ALIGN == e.lo % FST_RAW_ALIGN, so every source keeps the alignment it has
- *   in the file; the slot must hold slot_bytes.
+ *   e.slot_offset % FST_RAW_ALIGN == (e.lo + raw_base[f]) % FST_RAW_ALIGN, so every source has the
+ *   alignment it has in the resident layout; the slot must hold slot_bytes.
  *
  * Packed layout: the slot images of all groups side by side in one buffer of
  *   fst_plan_packed_bytes: group g's image starts at fst_group_info.packed_offset (a multiple of
@@ -232,7 +240,7 @@ typedef struct fst_group_info {
  * A compacted extent (n_rows > 1) stages n_rows segments of row_bytes, segment r being file bytes
  * [lo + r*stride, lo + r*stride + row_bytes), and its image holds them back to back
  * (n_rows*row_bytes bytes); hi is the end of the last segment.  Either image starts at slot_offset,
- * with slot_offset % FST_RAW_ALIGN == lo % FST_RAW_ALIGN.  Plain extents of a group are ascending
+ * with slot_offset % FST_RAW_ALIGN == (lo + raw_base[file]) % FST_RAW_ALIGN.  Plain extents of a group are ascending
  * and disjoint; compacted ones may lie inside the file range of others.
  */
 typedef struct fst_extent {

@@ -82,6 +82,7 @@ _SIGNATURES = {
     "fst_header_tensor": (c_int, [c_void_p, c_size_t, POINTER(fst_tensor_info)]),
     "fst_header_find": (c_int64, [c_void_p, c_char_p]),
     "fst_header_body_offset": (c_uint64, [c_void_p]),
+    "fst_aligned_phase": (c_uint64, [c_void_p]),
     "fst_header_file_size": (c_uint64, [c_void_p]),
     "fst_header_metadata_count": (c_size_t, [c_void_p]),
     "fst_header_metadata": (c_int, [c_void_p, c_size_t, POINTER(c_char_p), POINTER(c_char_p)]),
@@ -197,6 +198,9 @@ class Header:
 
     def body_offset(self) -> int:
         return lib().fst_header_body_offset(self._h)
+
+    def aligned_phase(self) -> int:
+        return lib().fst_aligned_phase(self._h)
 
     def file_size(self) -> int:
         return lib().fst_header_file_size(self._h)

@@ -108,6 +108,7 @@ struct Extent {
 
 struct Group {
     uint32_t file = 0;
+    uint64_t phase = 0;                     // raw_base[file] % 256: file byte x sits at an address = x + phase (mod 256) in every layout
     uint64_t lo = 0, hi = 0;                // first and last+1 staged file byte
     std::vector<Extent> extents;            // plain extents, ascending and disjoint, then the compacted ones
     std::map<uint64_t, uint64_t> plain;     // while the group is built: plain ranges lo -> hi (extents: compacted only)

@@ -489,6 +489,10 @@ int64_t fst_header_find(const fst_header *h, const char *name)
 }
 
 uint64_t fst_header_body_offset(const fst_header *h) { return h ? 8 + h->n_json : 0; }
+uint64_t fst_aligned_phase(const fst_header *h)
+{
+    return h ? (FST_RAW_ALIGN - (8 + h->n_json) % FST_RAW_ALIGN) % FST_RAW_ALIGN : 0;
+}
 uint64_t fst_header_file_size(const fst_header *h) { return h ? h->file_size : 0; }
 size_t fst_header_metadata_count(const fst_header *h) { return h ? h->metadata.size() : 0; }
 

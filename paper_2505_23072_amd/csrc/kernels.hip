@@ -84,8 +84,13 @@ __device__ __forceinline__ u32x4 load16(const uint8_t *src)
     return r;
 }
 
-// 8 bytes (in .x and .y) from any address (BYTE) or from a 4-byte aligned one.
-template <bool BYTE>
+// 8 bytes (in .x and .y) from any address (BYTE) or from a 4-byte aligned one.  The dword that holds
+// the last wanted bytes of an unaligned chunk is fetched only when there is one (the byte offset is
+// not 0): either in the same instruction as the others (FUSED: one of two load forms behind a
+// branch; best when a wavefront's lanes all have the same offset, as in the vector path: 6.15 against
+// 5.7 TB/s on BF16 -> F32) or with a predicated load of its own (no branch; best in the spliced path,
+// where the offset changes from row to row: 5.4 against 4.75 TB/s on 2050-byte row segments).
+template <bool BYTE, bool FUSED>
 __device__ __forceinline__ u32x4 load8(const uint8_t *src)
 {
     u32x4 r = {0u, 0u, 0u, 0u};
@@ -98,8 +103,12 @@ __device__ __forceinline__ u32x4 load8(const uint8_t *src)
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
     const uint32_t sh = uint32_t(a) & 3u;
     const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
-    // three dwords in one load when the third holds wanted bytes, two otherwise
-    if (sh) {
+    if (!FUSED) {
+        const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
+        const uint32_t e = sh ? gload4(p + 8) : 0u;
+        r.x = shift_bytes(v.y, v.x, sh);
+        r.y = shift_bytes(e, v.y, sh);
+    } else if (sh) {
         const u32x3 v = *(const FST_GLOBAL u32x3_a4 *)(p);
         r.x = shift_bytes(v.y, v.x, sh);
         r.y = shift_bytes(v.z, v.y, sh);
@@ -111,8 +120,8 @@ __device__ __forceinline__ u32x4 load8(const uint8_t *src)
     return r;
 }
 
-// 4 bytes (in .x) from any address (BYTE) or from a 4-byte aligned one.
-template <bool BYTE>
+// 4 bytes (in .x) from any address (BYTE) or from a 4-byte aligned one; FUSED as in load8.
+template <bool BYTE, bool FUSED>
 __device__ __forceinline__ u32x4 load4(const uint8_t *src)
 {
     u32x4 r = {0u, 0u, 0u, 0u};
@@ -123,7 +132,11 @@ __device__ __forceinline__ u32x4 load4(const uint8_t *src)
     const uintptr_t a = reinterpret_cast<uintptr_t>(src);
     const uint32_t sh = uint32_t(a) & 3u;
     const uint8_t *p = reinterpret_cast<const uint8_t *>(a & ~uintptr_t(3));
-    if (sh) {                                            // the second dword only if it holds wanted bytes
+    if (!FUSED) {
+        const uint32_t v = gload4(p);
+        const uint32_t e = sh ? gload4(p + 4) : 0u;      // the second dword only if it holds wanted bytes
+        r.x = shift_bytes(e, v, sh);
+    } else if (sh) {
         const u32x2 v = *(const FST_GLOBAL u32x2_a4 *)(p);
         r.x = shift_bytes(v.y, v.x, sh);
     } else {
@@ -688,12 +701,12 @@ __device__ __forceinline__ bool wave_tile(const DevDesc *__restrict__ descs, con
     return true;
 }
 
-template <uint32_t CS, bool BYTE>
+template <uint32_t CS, bool BYTE, bool FUSED>
 __device__ __forceinline__ Chunk32 load_chunk(const uint8_t *s)
 {
     Chunk32 v;
-    if (CS == 4) v.lo = load4<BYTE>(s);
-    else if (CS == 8) v.lo = load8<BYTE>(s);
+    if (CS == 4) v.lo = load4<BYTE, FUSED>(s);
+    else if (CS == 8) v.lo = load8<BYTE, FUSED>(s);
     else if (CS == 16) v.lo = load16<BYTE>(s);
     else v = load32<BYTE>(s);
     return v;
@@ -721,7 +734,7 @@ __device__ __forceinline__ void vec_chunk(const uint8_t *src, uint8_t *dst, uint
         const uint32_t r = fast_div(c, d.div_m(), d.div_s());
         s = src + uint64_t(r) * d.src_stride() + uint64_t(c - r * upr) * CS;
     }
-    const Chunk32 o = convert_chunk<CONV>(load_chunk<CS, BYTE>(s));
+    const Chunk32 o = convert_chunk<CONV>(load_chunk<CS, BYTE, true>(s));
     store_chunk<CD>(dst + uint64_t(c) * CD, o);
 }
 
@@ -792,11 +805,11 @@ __global__ __launch_bounds__(VEC_BLOCK_THREADS) void materialize_splice(const De
     const uint32_t r = fast_div(u0, d.div_m(), d.div_s());
     const uint32_t col = u0 - r * upr;
     const uint8_t *row = raw + d.src_off() + uint64_t(r) * d.src_stride();
-    Chunk32 v = load_chunk<CS, true>(row + uint64_t(col) * US);
+    Chunk32 v = load_chunk<CS, true, false>(row + uint64_t(col) * US);
     const uint32_t k = upr - col;                                       // units left in row r
     if (k < CH) {
         const uint8_t *next = row + d.src_stride() - k * US;
-        const Chunk32 w = load_chunk<CS, true>(next);
+        const Chunk32 w = load_chunk<CS, true, false>(next);
         v = splice_chunk<CS>(v, w, k * US);
     }
     const Chunk32 o = convert_chunk<CONV>(v);

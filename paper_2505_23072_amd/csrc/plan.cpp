@@ -102,8 +102,8 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
     const uint64_t relems = compact ? file_rows * file_relems : file_relems;
     const uint64_t src0 = compact ? 0 : file_src0;
     const uint64_t stride = rows > 1 ? o.src_stride : 0;
-    // source address modulo 256 of offset `off`: raw bases and slot images keep the file's phase
-    const uint64_t phase0 = compact ? g.extents[extent].lo : 0;       // (while a group is built, extents = the compacted ones)
+    // source address modulo 256 of offset `off`: file byte x sits at x + phase (mod 256) in every layout
+    const uint64_t phase0 = g.phase + (compact ? g.extents[extent].lo : 0);   // (while a group is built, extents = the compacted ones)
 
     // the kernels count in units: bytes when nothing is converted, elements otherwise
     const uint64_t unit_s = conv_src_bytes(conv), unit_d = conv_dst_bytes(conv);
@@ -216,10 +216,10 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
 
 uint64_t round_up_256(uint64_t v) { return (v + FST_RAW_ALIGN - 1) / FST_RAW_ALIGN * FST_RAW_ALIGN; }
 
-// Slot space of `bytes` staged bytes whose first one is file byte lo: the image starts at the file
-// phase (lo % 256) so sources keep their alignment, and the next image starts on the following
-// 256-byte boundary.
-uint64_t extent_space(uint64_t lo, uint64_t bytes) { return round_up_256(lo % FST_RAW_ALIGN + bytes); }
+// Slot space of `bytes` staged bytes whose first one is file byte lo: the image starts at the
+// phase the file's bytes have in every layout ((lo + phase) % 256), so a source has the same
+// alignment wherever it is staged, and the next image starts on the following 256-byte boundary.
+uint64_t extent_space(const Group &g, uint64_t lo, uint64_t bytes) { return round_up_256((lo + g.phase) % FST_RAW_ALIGN + bytes); }
 
 uint64_t sat_add(uint64_t a, uint64_t b) { return a > UINT64_MAX - b ? UINT64_MAX : a + b; }
 
@@ -242,7 +242,7 @@ Merge merge_of(const Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
     while (it != g.plain.end() && it->first <= sat_add(m.hi, min_gap)) {
         m.lo = std::min(m.lo, it->first);
         m.hi = std::max(m.hi, it->second);
-        m.absorbed_space += extent_space(it->first, it->second - it->first);
+        m.absorbed_space += extent_space(g, it->first, it->second - it->first);
         ++it;
     }
     m.last = it;
@@ -253,13 +253,13 @@ Merge merge_of(const Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
 uint64_t space_with(const Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
 {
     const Merge m = merge_of(g, s_lo, s_hi, min_gap);
-    return g.slot_bytes - m.absorbed_space + extent_space(m.lo, m.hi - m.lo);
+    return g.slot_bytes - m.absorbed_space + extent_space(g, m.lo, m.hi - m.lo);
 }
 
 void add_range(Group &g, uint64_t s_lo, uint64_t s_hi, uint64_t min_gap)
 {
     const Merge m = merge_of(g, s_lo, s_hi, min_gap);
-    g.slot_bytes = g.slot_bytes - m.absorbed_space + extent_space(m.lo, m.hi - m.lo);
+    g.slot_bytes = g.slot_bytes - m.absorbed_space + extent_space(g, m.lo, m.hi - m.lo);
     g.plain.erase(m.first, m.last);
     g.plain[m.lo] = m.hi;
     g.lo = g.hi == 0 ? s_lo : std::min(g.lo, s_lo);        // hi == 0: the group's first range
@@ -276,7 +276,7 @@ size_t add_compact(Group &g, uint64_t lo, uint64_t row_bytes, uint64_t n_rows, u
     e.row_bytes = row_bytes;
     e.n_rows = n_rows;
     e.stride = n_rows > 1 ? stride : 0;
-    g.slot_bytes += extent_space(lo, n_rows * row_bytes);
+    g.slot_bytes += extent_space(g, lo, n_rows * row_bytes);
     g.lo = g.hi == 0 ? lo : std::min(g.lo, lo);
     g.hi = std::max(g.hi, e.hi);
     g.extents.push_back(e);
@@ -304,8 +304,8 @@ int close_group(fst_plan *p, Group &g, size_t desc_begin)
     g.plain.clear();
     uint64_t at = 0;
     for (Extent &e : g.extents) {
-        e.slot_off = at + e.lo % FST_RAW_ALIGN;
-        at += extent_space(e.lo, e.image_bytes());
+        e.slot_off = at + (e.lo + g.phase) % FST_RAW_ALIGN;
+        at += extent_space(g, e.lo, e.image_bytes());
     }
     g.slot_bytes = at;
     for (Piece &pc : g.pieces) {
@@ -328,7 +328,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap, uint64_t min
 {
     if (max_bytes != 0 && max_bytes < kMinGroupBytes)
         return fail(FST_E_ARG, "max_group_bytes must be 0 or at least %llu", (unsigned long long)kMinGroupBytes);
-    // in a slot an extent starts at its file phase (up to 255 bytes) and is padded to 256
+    // in a slot an extent starts at its phase (up to 255 bytes) and is padded to 256
     const uint64_t budget = max_bytes ? max_bytes - 2 * (FST_RAW_ALIGN - 1) : UINT64_MAX;
     {
         std::lock_guard<std::mutex> lock(p->image_mu);
@@ -359,6 +359,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap, uint64_t min
         auto start = [&]() {
             G.emplace_back();
             G.back().file = f;
+            G.back().phase = p->raw_base[f] % FST_RAW_ALIGN;
             desc_begin = p->descs.size();
             open = true;
         };
@@ -390,7 +391,7 @@ int build_groups(fst_plan *p, uint64_t max_bytes, uint64_t min_gap, uint64_t min
                         if (int rc = add_work(p, G.back(), oi, r, r + 1, 0, 0)) return rc;
                         continue;
                     }
-                    if (open && max_bytes && G.back().slot_bytes + extent_space(c_lo, nr * row_bytes) > max_bytes) finish();
+                    if (open && max_bytes && G.back().slot_bytes + extent_space(G.back(), c_lo, nr * row_bytes) > max_bytes) finish();
                     if (!open) start();
                     const size_t ex = add_compact(G.back(), c_lo, row_bytes, nr, o.src_stride);
                     if (int rc = add_work(p, G.back(), oi, r, r + nr, 0, 0, ex, true)) return rc;
@@ -486,8 +487,6 @@ int plan_impl(const fst_header *const *hdrs, const uint64_t *raw_base, size_t n_
     p->n_files = n_files;
     for (size_t f = 0; f < n_files; ++f) {
         if (!hdrs[f]) return fail(FST_E_ARG, "header %zu is NULL", f);
-        if (raw_base[f] % FST_RAW_ALIGN)
-            return fail(FST_E_ALIGN, "raw_base[%zu] is not a multiple of %d", f, FST_RAW_ALIGN);
         p->raw_base.push_back(raw_base[f]);
         p->file_size.push_back(hdrs[f]->file_size);
     }

@@ -42,13 +42,22 @@ def read_header(path: str) -> Tuple[B.Header, int]:
     return B.Header(head, size), size
 
 
-def file_bases(sizes: Sequence[int]) -> Tuple[List[int], int]:
-    """Offsets at which whole files sit in one raw buffer, each a multiple of 256, and its length."""
+def file_bases(sizes: Sequence[int], headers: Optional[Sequence[B.Header]] = None) -> Tuple[List[int], int]:
+    """Offsets at which whole files sit in one raw buffer, and its length.  Without headers every file starts on a
+    multiple of 256; with them every file is shifted so that its tensor data (the first byte after the header)
+    starts on one, which lets the kernels read most tensors with aligned loads."""
     bases, at = [], 0
-    for s in sizes:
-        bases.append(at)
-        at += (s + 255) // 256 * 256
+    for i, s in enumerate(sizes):
+        phase = headers[i].aligned_phase() if headers is not None else 0
+        bases.append(at + phase)
+        at += (phase + s + 255) // 256 * 256
     return bases, max(at, 256)
+
+
+def file_phases(headers: Sequence[B.Header]) -> List[int]:
+    """raw_base values for plans that are only staged into slots or packed: just the phase that aligns each file's
+    tensor data."""
+    return [h.aligned_phase() for h in headers]
 
 
 def alloc_outputs(plan: B.Plan, dev: Optional[torch.device] = None) -> Tuple[List[torch.Tensor], List[int]]:
@@ -78,7 +87,7 @@ def load_files(paths: Sequence[str], requests: Optional[Dict[str, B.Request]] = 
         h, s = read_header(p)
         headers.append(h)
         sizes.append(s)
-    bases, raw_len = file_bases(sizes)
+    bases, raw_len = file_bases(sizes, headers)
     if requests is None:
         requests = {t["name"]: (None, -1, 1) for h in headers for t in h.tensors()}
     names = list(requests)

@@ -215,7 +215,7 @@ class SafeTensorsFileLoader:
             sizes.append(s)
         if not self._requests:
             # the paper's way: whole files, verbatim, resident
-            bases, raw_len = D.file_bases(sizes)
+            bases, raw_len = D.file_bases(sizes, headers)        # every file's tensor data on a 256-byte boundary
             names = [t["name"] for h in headers for t in h.tensors()]
             plan = B.Plan(headers, bases, names, [(None, -1, 1)] * len(names))
             plan.set_groups(self._group_bytes)
@@ -229,7 +229,7 @@ class SafeTensorsFileLoader:
         else:
             names = list(self._requests)
             reqs = [self._requests[n] for n in names]
-            plan = B.Plan(headers, [0] * len(headers), names, reqs, self._group.rank(), self._group.size())
+            plan = B.Plan(headers, D.file_phases(headers), names, reqs, self._group.rank(), self._group.size())
             try:
                 slot_bytes = stream_slots[1] if stream_slots else self._group_bytes
                 plan.set_groups(slot_bytes, self._min_gap, self._min_seg)

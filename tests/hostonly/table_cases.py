@@ -58,14 +58,25 @@ def slot_image(gi, blobs):
     return host
 
 
-def run(blobs, names, reqs, rank, world, layout, max_group_bytes=0, min_gap=None, min_seg=None, per_group=False):
+def run(blobs, names, reqs, rank, world, layout, max_group_bytes=0, min_gap=None, min_seg=None, per_group=False,
+        phases=None):
+    """phases: per file, where its bytes sit modulo 256 (None: at their file offsets' residues; "aligned": tensor
+    data on a 256-byte boundary; or a list)."""
     hs = headers_of(blobs)
     sizes = [len(b) for b in blobs]
+    if phases is None:
+        phases = [0] * len(blobs)
+    elif phases == "aligned":
+        phases = [h.aligned_phase() for h in hs]
     bases, at = [], 0
-    for n in sizes:
-        bases.append(at)
-        at += (n + 255) // 256 * 256
-    plan = B.Plan(hs, bases if layout == B.FST_LAYOUT_RESIDENT else [0] * len(blobs), names, reqs, rank, world)
+    for n, ph in zip(sizes, phases):
+        bases.append(at + ph)
+        at += (ph + n + 255) // 256 * 256
+    plan = B.Plan(hs, bases if layout == B.FST_LAYOUT_RESIDENT else phases, names, reqs, rank, world)
+    for g in range(plan.group_count()):
+        gi = plan.group(g)
+        for lo, hi, off in gi["extents"]:
+            assert off % 256 == (lo + phases[gi["file"]]) % 256
     plan.set_groups(max_group_bytes, min_gap, min_seg)
     keep, outs, ptrs = [], [], []
     L.fst_test_clear_outputs()
@@ -127,12 +138,16 @@ LAYOUTS = [
 
 
 def check_all(blobs, names, reqs, rank, world, layouts=LAYOUTS, tag=""):
+    """Every layout with every file at its own residues, and again with the files shifted: tensor data aligned
+    for the even layouts, an arbitrary phase per file for the odd ones."""
     want = oracle_outputs(blobs, names, reqs, rank, world)
-    for kw in layouts:
-        got, plan = run(blobs, names, reqs, rank, world, **kw)
-        for i, (g, w) in enumerate(zip(got, want)):
-            assert g == w, f"{tag} {kw} output {i} {names[i]} {reqs[i]}"
-        plan.close()
+    rng = np.random.default_rng(len(names) * 7919 + len(blobs[0]))
+    for k, kw in enumerate(layouts):
+        for phases in (None, "aligned" if k % 2 == 0 else [int(x) for x in rng.integers(0, 256, len(blobs))]):
+            got, plan = run(blobs, names, reqs, rank, world, phases=phases, **kw)
+            for i, (g, w) in enumerate(zip(got, want)):
+                assert g == w, f"{tag} {kw} phases {phases} output {i} {names[i]} {reqs[i]}"
+            plan.close()
 
 
 @pytest.mark.parametrize("seed", range(8))

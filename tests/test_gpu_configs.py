@@ -111,10 +111,16 @@ def _picks(spec, names, layers):
     return keep
 
 
-def _run_resident(spec, layers, group_bytes=GB):
+def _headers(model):
+    return [B.Header(h, s) for h, s in zip(model.headers, model.sizes)]
+
+
+def _run_resident(spec, layers, group_bytes=GB, aligned=False):
+    """aligned: every file shifted so that its tensor data starts on a 256-byte boundary of the raw buffer (what
+    bench.py and the loader do); otherwise every byte at its file offset's residue."""
     t0 = time.time()
     model = ProceduralModel(spec)
-    bases, raw_len = device.file_bases(model.sizes)
+    bases, raw_len = device.file_bases(model.sizes, _headers(model) if aligned else None)
     plan, names, reqs = _plan(model, spec, bases)
     plan.set_groups(group_bytes)
     raw = device.device_bytes(raw_len)
@@ -154,7 +160,9 @@ def _run_resident(spec, layers, group_bytes=GB):
 def _run_streamed(spec, dev_slots, slot_bytes, min_gap=None, min_seg=None):
     t0 = time.time()
     model = ProceduralModel(spec)
-    plan, names, reqs = _plan(model, spec, [0] * len(model.sizes))
+    # the compacted staging is the one bench.py times: like it, with every file's tensor data aligned
+    phases = device.file_phases(_headers(model)) if min_seg is not None else [0] * len(model.sizes)
+    plan, names, reqs = _plan(model, spec, phases)
     ng = plan.set_groups(slot_bytes, min_gap, min_seg)
     slots = [device.device_bytes(slot_bytes) for _ in range(dev_slots)]
     ws = device.device_bytes(plan.workspace_bytes())
@@ -174,15 +182,17 @@ def _run_streamed(spec, dev_slots, slot_bytes, min_gap=None, min_seg=None):
     return plan, stats
 
 
-def test_config2_llama7b_resident():
+@pytest.mark.parametrize("aligned", [False, True])
+def test_config2_llama7b_resident(aligned):
     spec = specs.config2_llama7b()
-    plan = _run_resident(spec, layers=[0, 23, 24, 31])
+    plan = _run_resident(spec, layers=[0, 23, 24, 31], aligned=aligned)
     assert plan.output_count() == 291 and plan.read_bytes() == plan.write_bytes() == 13_476_831_232
 
 
-def test_config3_llama13b_fp16_to_bf16():
+@pytest.mark.parametrize("aligned", [False, True])
+def test_config3_llama13b_fp16_to_bf16(aligned):
     spec = specs.config3_llama13b()
-    plan = _run_resident(spec, layers=[0, 13, 39])
+    plan = _run_resident(spec, layers=[0, 13, 39], aligned=aligned)
     assert plan.output_count() == 363 and plan.read_bytes() == plan.write_bytes() == 26_031_728_640
     assert plan.output(5)["dtype"] == "BF16"
 

@@ -52,6 +52,16 @@ def test_random_files(seed):
     assert plan.packed_bytes() == sum(plan.group(g)["slot_bytes"] for g in range(plan.group_count()))
     got, _ = materialize_packed(blobs, names, reqs, rank, world)
     _check(got, want, names, reqs, "packed, one group per file")
+    # the files shifted in device memory: tensor data on a 256-byte boundary, and an arbitrary phase per file
+    for phases in ("aligned", [int(x) for x in rng.integers(0, 256, len(blobs))]):
+        got, _ = materialize_resident(blobs, names, reqs, rank, world, phases=phases)
+        _check(got, want, names, reqs, f"all-groups, phases {phases}")
+        got, _ = materialize_resident(blobs, names, reqs, rank, world, max_group_bytes=0, min_gap_bytes=0, phases=phases)
+        _check(got, want, names, reqs, f"sparse resident, phases {phases}")
+        got, _ = materialize_slots(blobs, names, reqs, rank, world, 16384, min_gap_bytes=300, min_segment_bytes=2, phases=phases)
+        _check(got, want, names, reqs, f"compacted slots, phases {phases}")
+        got, _ = materialize_packed(blobs, names, reqs, rank, world, 1 << 16, min_gap_bytes=0, min_segment_bytes=64, phases=phases)
+        _check(got, want, names, reqs, f"compacted, packed, phases {phases}")
 
 
 # several tiles (a tile is 16 KiB of output) and a ragged tail

@@ -14,7 +14,7 @@ from synth import specs
 from synth.source import ProceduralModel
 from synth import writer
 from util_cases import make_file, random_bits, random_request
-from util_gpu import first_diff, headers_of, oracle_outputs
+from util_gpu import bases_of, first_diff, headers_of, oracle_outputs, phases_of
 
 pytestmark = pytest.mark.gpu
 
@@ -59,7 +59,9 @@ def test_resident_ring(seed, slots, threads, slot_bytes, group_bytes, gap, tmp_p
     print(f"seed {seed} ring {slots}x{slot_bytes} threads {threads} groups {group_bytes}", flush=True)
     want = oracle_outputs(blobs, names, reqs, rank, world)
     hs = headers_of(blobs)
-    bases, raw_len = device.file_bases([len(b) for b in blobs])
+    # the files at their own residues, with their tensor data on a 256-byte boundary, or at any phase
+    phases = (None, "aligned", [(37 * seed + 11 * f) % 256 for f in range(len(blobs))])[seed % 3]
+    bases, raw_len = bases_of(blobs, phases)
     plan = B.Plan(hs, bases, names, reqs, rank, world)
     plan.set_groups(group_bytes, gap)
     raw = device.device_bytes(raw_len)
@@ -102,7 +104,8 @@ def test_streamed_ring(seed, dev_slots, group_bytes, gap, tmp_path):
     print(f"seed {seed} device slots {dev_slots}x{group_bytes}", flush=True)
     want = oracle_outputs(blobs, names, reqs, rank, world)
     hs = headers_of(blobs)
-    plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
+    phases = phases_of(blobs, (None, "aligned", [(37 * seed + 11 * f) % 256 for f in range(len(blobs))])[seed % 3])
+    plan = B.Plan(hs, phases, names, reqs, rank, world)
     ng = plan.set_groups(group_bytes, gap)
     assert ng > len(blobs)
     slots = [device.device_bytes(group_bytes) for _ in range(dev_slots)]

@@ -16,9 +16,27 @@ def headers_of(blobs):
     return hs
 
 
-def upload_resident(blobs, sparse_plan=None):
+def phases_of(blobs, phases):
+    """Per file, where its bytes sit modulo 256 in device memory: None = at their file offsets' residues,
+    "aligned" = tensor data on a 256-byte boundary, or a list."""
+    if phases is None:
+        return [0] * len(blobs)
+    if phases == "aligned":
+        return [h.aligned_phase() for h in headers_of(blobs)]
+    return list(phases)
+
+
+def bases_of(blobs, phases=None):
+    bases, at = [], 0
+    for b, ph in zip(blobs, phases_of(blobs, phases)):
+        bases.append(at + ph)
+        at += (ph + len(b) + 255) // 256 * 256
+    return bases, max(at, 256)
+
+
+def upload_resident(blobs, sparse_plan=None, phases=None):
     """Whole files in the raw buffer; with sparse_plan only that plan's extents (0xDD elsewhere)."""
-    bases, raw_len = device.file_bases([len(b) for b in blobs])
+    bases, raw_len = bases_of(blobs, phases)
     if sparse_plan is None:
         host = np.zeros(raw_len, np.uint8)
         for b, at in zip(blobs, bases):
@@ -42,13 +60,13 @@ def fetch(bufs, plan):
 
 
 def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=None, per_group=False, stream=None,
-                         min_gap_bytes=None):
+                         min_gap_bytes=None, phases=None):
     """Resident layout; one call for all groups, or one call per group."""
     hs = headers_of(blobs)
-    plan = B.Plan(hs, device.file_bases([len(b) for b in blobs])[0], names, reqs, rank, world)
+    plan = B.Plan(hs, bases_of(blobs, phases)[0], names, reqs, rank, world)
     if max_group_bytes is not None:
         plan.set_groups(max_group_bytes, min_gap_bytes)
-    raw, bases, raw_len = upload_resident(blobs, plan if min_gap_bytes is not None else None)
+    raw, bases, raw_len = upload_resident(blobs, plan if min_gap_bytes is not None else None, phases)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
         b.fill_(0xA5)
@@ -64,13 +82,14 @@ def materialize_resident(blobs, names, reqs, rank=0, world=1, max_group_bytes=No
     return fetch(bufs, plan), plan
 
 
-def slot_image(gi, blobs, fill=0xEE):
+def slot_image(gi, blobs, fill=0xEE, phases=None):
     """The slot image of one group, built on the host from the file bytes: plain extents verbatim, compacted
     extents as their row segments back to back; bytes between the extents keep `fill`."""
     host = np.full(gi["slot_bytes"], fill, np.uint8)
     data = np.frombuffer(blobs[gi["file"]], np.uint8)
+    phase = phases[gi["file"]] if phases is not None else 0
     for (lo, hi, off), (row_bytes, n_rows, stride) in zip(gi["extents"], gi["extent_rows"]):
-        assert off % 256 == lo % 256
+        assert off % 256 == (lo + phase) % 256
         if n_rows == 1:
             assert row_bytes == hi - lo
             host[off:off + hi - lo] = data[lo:hi]
@@ -81,10 +100,12 @@ def slot_image(gi, blobs, fill=0xEE):
     return host
 
 
-def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_bytes=None, min_segment_bytes=None):
+def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_bytes=None, min_segment_bytes=None,
+                      phases=None):
     """Slot layout: every group's extents alone in a slot buffer, each at its slot offset."""
     hs = headers_of(blobs)
-    plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
+    phases = phases_of(blobs, phases)
+    plan = B.Plan(hs, phases, names, reqs, rank, world)
     plan.set_groups(max_group_bytes, min_gap_bytes, min_segment_bytes)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
@@ -94,17 +115,18 @@ def materialize_slots(blobs, names, reqs, rank, world, max_group_bytes, min_gap_
     for g in range(plan.group_count()):
         gi = plan.group(g)
         assert gi["slot_bytes"] <= max_group_bytes
-        slot[:gi["slot_bytes"]].copy_(torch.from_numpy(slot_image(gi, blobs)))
+        slot[:gi["slot_bytes"]].copy_(torch.from_numpy(slot_image(gi, blobs, phases=phases)))
         B.fst_materialize_slot(slot.data_ptr(), gi["slot_bytes"], plan, g, ptrs, ws.data_ptr(), ws.numel(), 0)
         torch.cuda.synchronize()
     return fetch(bufs, plan), plan
 
 
 def materialize_packed(blobs, names, reqs, rank=0, world=1, max_group_bytes=0, min_gap_bytes=None,
-                       min_segment_bytes=None):
+                       min_segment_bytes=None, phases=None):
     """Packed layout: the slot images of all groups side by side in one buffer, one launch set for all."""
     hs = headers_of(blobs)
-    plan = B.Plan(hs, [0] * len(blobs), names, reqs, rank, world)
+    phases = phases_of(blobs, phases)
+    plan = B.Plan(hs, phases, names, reqs, rank, world)
     plan.set_groups(max_group_bytes, min_gap_bytes, min_segment_bytes)
     bufs, ptrs = device.alloc_outputs(plan)
     for b in bufs:
@@ -116,7 +138,7 @@ def materialize_packed(blobs, names, reqs, rank=0, world=1, max_group_bytes=0, m
     for g in range(plan.group_count()):
         gi = plan.group(g)
         assert gi["packed_offset"] == at and at % 256 == 0
-        host[at:at + gi["slot_bytes"]] = slot_image(gi, blobs)
+        host[at:at + gi["slot_bytes"]] = slot_image(gi, blobs, phases=phases)
         at += gi["slot_bytes"]
     assert at == n
     packed = device.device_bytes(len(host))
