@@ -431,8 +431,10 @@ def run_config(spec, args, freed_before, micro=False):
                          "gbps": round(nbytes[g] / (spans[:, g].mean() * 1e-3) / 1e9, 1)} for g in range(ng0)]
             dom_ms, dom_min, dom_bytes = float(spans[:, dom].mean()), float(spans[:, dom].min()), nbytes[dom]
         else:
-            kernel = ("all materialize kernels of one step: one launch set over every file (materialize_vec<COPY> with "
-                      "byte- and dword-aligned sources carries the bytes; the conversions and tails are small launches)")
+            variants = ("its variant for 4-byte aligned sources" if getattr(args, "file_phase", "aligned") == "aligned"
+                        else "its variants for byte- and 4-byte aligned sources")
+            kernel = (f"all materialize kernels of one step: one launch set over every file (materialize_vec<COPY>, {variants}, "
+                      "carries the bytes; the conversions and tails are small launches)")
             dom_ms, dom_min, dom_bytes = float(spans[:, 0].mean()), float(spans[:, 0].min()), rd + wr
             launches = [{"files": "all", "bytes": dom_bytes, "ms_avg": round(dom_ms, 4),
                          "gbps": round(dom_bytes / (dom_ms * 1e-3) / 1e9, 1)}]
