@@ -225,6 +225,71 @@ def test_config5_bloom176b_tp8_rank0_streamed(min_gap, min_seg):
         assert stats["staged_bytes"] <= 1.1 * plan.read_bytes()
 
 
+def _run_as_benchmarked(spec, layers):
+    """The two launch configurations bench.py times for a tensor-parallel configuration, files placed with their
+    tensor data aligned.  End to end: what the rank reads, sparse and compacted, staged into the packed layout and
+    materialized group by group while it is staged; every output is compared.  Kernel leg: all staged bytes
+    in device memory first (whole files resident when they fit beside the outputs, else the sparse packed layout
+    with row-split tensors whole), then one merged launch set over every group; sampled layers are compared."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()            # the buffers below need most of the device
+    model = ProceduralModel(spec)
+    hs = _headers(model)
+    phases = device.file_phases(hs)
+    st = B.Stager(8, 12, 128 << 20)
+    try:
+        # end to end
+        plan, names, reqs = _plan(model, spec, phases)
+        plan.set_groups(GB, 1 << 20, 2048)
+        n = plan.packed_bytes()
+        packed = device.device_bytes(n)
+        ws = device.device_bytes(plan.workspace_bytes())
+        bufs, ptrs = device.alloc_outputs(plan)
+        stats = st.stage_packed(plan, model.read_fn, model.ctx, packed.data_ptr(), n, ptrs, ws.data_ptr(), ws.numel())
+        assert stats["staged_bytes"] <= 1.01 * plan.read_bytes()
+        print(f"{spec.name}: packed, sparse + compacted: staged {stats['staged_bytes'] / 1e9:.2f} GB in {stats['seconds_total']:.2f}s, "
+              f"{plan.group_count()} groups", flush=True)
+        _check_all(model, spec, plan, bufs, names, reqs)
+        plan.close()
+        del packed, ws
+        for b in bufs:
+            b.zero_()
+        gc.collect()
+        torch.cuda.empty_cache()
+        # kernel leg
+        bases, raw_len = device.file_bases(model.sizes, hs)
+        resident = raw_len + sum(b.numel() for b in bufs) <= 230 * GB
+        plan, names, reqs = _plan(model, spec, bases if resident else phases)
+        plan.set_groups(GB, None if resident else 1 << 20)
+        n = raw_len if resident else plan.packed_bytes()
+        src = device.device_bytes(n)
+        ws = device.device_bytes(plan.workspace_bytes())
+        fn = st.stage_resident if resident else st.stage_packed
+        fn(plan, model.read_fn, model.ctx, src.data_ptr(), n, ptrs, ws.data_ptr(), ws.numel(), B.FST_STAGE_NO_KERNELS)
+        layout = B.FST_LAYOUT_RESIDENT if resident else B.FST_LAYOUT_PACKED
+        B.fst_prepare(plan, B.FST_ALL_GROUPS, layout, n, ptrs, ws.data_ptr(), ws.numel(), 0)
+        B.fst_launch(plan, B.FST_ALL_GROUPS, src.data_ptr(), n, 0)
+        torch.cuda.synchronize()
+        print(f"{spec.name}: kernel leg from the {'resident' if resident else 'packed sparse'} layout, {n / 1e9:.1f} GB staged, "
+              f"{plan.group_count()} groups in one launch set", flush=True)
+        _check_sample(model, spec, plan, bufs, names, reqs, _picks(spec, names, layers))
+        plan.close()
+        del src, ws, bufs
+    finally:
+        st.close()
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
+def test_config4_llama70b_as_benchmarked():
+    _run_as_benchmarked(specs.config4_llama70b(), layers=[0, 41, 79])
+
+
+def test_config5_bloom176b_as_benchmarked():
+    _run_as_benchmarked(specs.config5_bloom176b(), layers=[0, 35, 69])
+
+
 def test_falcon40b_tp2_rank0_streamed_sparse():
     """A second workload from the paper's Table I (Falcon-40B, 9 files, loaded on two GPUs there)."""
     spec = specs.config_falcon40b()
