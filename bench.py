@@ -450,7 +450,7 @@ def run_config(spec, args, freed_before, micro=False):
             res["roofline"]["achieved"], "GB/s")
         res["device_bytes_held"] = int(torch.cuda.max_memory_allocated())
         del buf, wss, ws
-        if getattr(args, "file_phase", "aligned") == "aligned" and not micro:
+        if getattr(args, "file_phase", "aligned") == "aligned" and not micro and not args.no_residues:
             # The same kernels with every byte at its file offset's residue, as a loader that does not place the files
             # would leave them: files whose header length is not a multiple of 4 then take the kernel variant for
             # byte-aligned sources.  Kernels alone (tables uploaded once, HIP events around fst_launch).
@@ -654,6 +654,8 @@ def main() -> int:
     ap.add_argument("--file-phase", choices=("aligned", "keep"), default="aligned",
                     help="where a file's bytes sit in device memory modulo 256: 'aligned' shifts every file so that its tensor "
                          "data starts on a 256-byte boundary, 'keep' leaves every byte at its file offset's residue")
+    ap.add_argument("--no-residues", action="store_true",
+                    help="skip the second kernel measurement of every configuration (files at their own residues)")
     ap.add_argument("--group-bytes", type=int, default=1 << 30)
     ap.add_argument("--min-gap", type=int, default=1 << 20,
                     help="sparse staging (tensor-parallel configurations): unread file ranges longer than this are not staged")

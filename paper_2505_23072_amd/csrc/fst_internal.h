@@ -217,9 +217,29 @@ constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;
 constexpr uint64_t SPLICE_PIECE_MAX_UNITS = (1ull << 31) - 64;
 
 uint32_t conv_kind(int src_dtype, int dst_dtype);            // CONV_*; CONV_COUNT if unsupported
-uint32_t conv_src_bytes(uint32_t conv);                       // bytes per source element (1 for COPY)
-uint32_t conv_dst_bytes(uint32_t conv);
-uint32_t conv_chunk_elems(uint32_t conv);                     // elements per chunk; 16 (bytes) for COPY
+// Geometry of a conversion, shared by the planner and the kernels: bytes per source and per result
+// element (COPY moves bytes: 1 and 1), and the elements of a chunk, which is what a lane moves with
+// one 16-byte store when the conversion widens, and 8 elements (4 from binary64) when it narrows or
+// keeps the width; COPY: 16 bytes.
+constexpr uint32_t conv_src_bytes(uint32_t c)
+{
+    return (c == CONV_COPY || (c >= CONV_E5H && c <= CONV_E4F)) ? 1
+         : (c == CONV_D2F || c == CONV_D2H || c == CONV_D2B) ? 8
+         : (c == CONV_F2H || c == CONV_F2B || c == CONV_F2D) ? 4 : 2;
+}
+constexpr uint32_t conv_dst_bytes(uint32_t c)
+{
+    return c == CONV_COPY ? 1
+         : (c == CONV_F2D || c == CONV_H2D || c == CONV_B2D) ? 8
+         : (c == CONV_H2F || c == CONV_B2F || c == CONV_D2F || c == CONV_E5F || c == CONV_E4F) ? 4 : 2;
+}
+constexpr uint32_t conv_chunk_elems(uint32_t c)
+{
+    return c == CONV_COPY ? 16
+         : conv_dst_bytes(c) > conv_src_bytes(c) ? 16 / conv_dst_bytes(c)
+         : conv_src_bytes(c) == 8 ? 4 : 8;
+}
+static_assert(CONV_E5H + 5 == CONV_E4F, "the 8-bit float conversions are numbered in a row");
 // Bytes of output a lane stores at once: 16, or 8 for binary64 -> 16-bit (4 elements of 2 bytes).
 // A piece's first output byte must be a multiple of it (16-byte aligned where the chunk is longer).
 inline uint32_t conv_store_align(uint32_t conv) { return conv == CONV_D2H || conv == CONV_D2B ? 8 : 16; }

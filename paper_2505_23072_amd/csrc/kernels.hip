@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstddef>
+#include <utility>
 
 #include "fst_internal.h"
 
@@ -298,31 +299,17 @@ __device__ __forceinline__ uint32_t e4m3_to_float(uint32_t b)
     return sign | r;
 }
 
-template <uint32_t CONV> struct ConvTraits;
 // SRC / DST: bytes of one chunk before and after; UNITS: units per chunk (bytes when copying).
-// A chunk is what one 16-byte store holds after a widening conversion, and 16 bytes to 8 or 4 after
-// a narrowing one: two 16-byte stores per lane, 32 bytes apart from lane to lane, ran at half to
-// two thirds of the rate of one store per lane (a bare kernel with that access shape reaches 3.2
-// TB/s against 6.2 to 6.5), while two loads per lane cost little.
-template <> struct ConvTraits<CONV_COPY> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 16; };
-template <> struct ConvTraits<CONV_H2B> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_B2H> { static constexpr uint32_t SRC = 16, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_H2F> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 4; };
-template <> struct ConvTraits<CONV_B2F> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 4; };
-template <> struct ConvTraits<CONV_F2H> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_F2B> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_D2F> { static constexpr uint32_t SRC = 32, DST = 16, UNITS = 4; };
-template <> struct ConvTraits<CONV_F2D> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 2; };
-template <> struct ConvTraits<CONV_D2H> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
-template <> struct ConvTraits<CONV_D2B> { static constexpr uint32_t SRC = 32, DST = 8, UNITS = 4; };
-template <> struct ConvTraits<CONV_H2D> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 2; };
-template <> struct ConvTraits<CONV_B2D> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 2; };
-template <> struct ConvTraits<CONV_E5H> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_E5B> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_E5F> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 4; };
-template <> struct ConvTraits<CONV_E4H> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_E4B> { static constexpr uint32_t SRC = 8, DST = 16, UNITS = 8; };
-template <> struct ConvTraits<CONV_E4F> { static constexpr uint32_t SRC = 4, DST = 16, UNITS = 4; };
+// A widening conversion's chunk is what one 16-byte store holds: two 16-byte stores per lane, 32
+// bytes apart from lane to lane, ran at half to two thirds of the rate of one store per lane (a bare
+// kernel with that access shape reaches 3.2 TB/s against 6.2 to 6.5), while two loads per lane, as
+// the narrowing conversions have, cost little.
+template <uint32_t CONV> struct ConvTraits {
+    static constexpr uint32_t UNITS = conv_chunk_elems(CONV);
+    static constexpr uint32_t SRC = UNITS * conv_src_bytes(CONV), DST = UNITS * conv_dst_bytes(CONV);
+    static_assert(SRC == 4 || SRC == 8 || SRC == 16 || SRC == 32, "chunk loads come in these sizes");
+    static_assert(DST == 8 || DST == 16, "one store per lane");
+};
 template <uint32_t CONV> constexpr bool from_e5m2 = CONV == CONV_E5H || CONV == CONV_E5B || CONV == CONV_E5F;
 template <uint32_t CONV> constexpr bool from_e4m3 = CONV == CONV_E4H || CONV == CONV_E4B || CONV == CONV_E4F;
 
@@ -987,6 +974,15 @@ int launch_conv(uint32_t path, bool byte_aligned, const DevDesc *descs, const ui
     return FST_OK;
 }
 
+// launch_conv<C> for the C that equals `conv`.
+template <uint32_t... C, typename... Args>
+int launch_any_conv(uint32_t conv, std::integer_sequence<uint32_t, C...>, Args... args)
+{
+    int rc = FST_E_ARG;
+    const bool found = ((conv == C ? (rc = launch_conv<C>(args...), true) : false) || ...);
+    return found ? rc : fail(FST_E_ARG, "unknown conversion %u", conv);
+}
+
 }  // namespace
 
 int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t *hints_dev, uint32_t n_tiles,
@@ -998,28 +994,8 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs_dev, const uint32_t 
     const bool byte_aligned = path == PATH_VEC && cls % 2 == 1;
     const uint8_t *raw = static_cast<const uint8_t *>(raw_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    switch (conv) {
-    case CONV_COPY: return launch_conv<CONV_COPY>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_H2B: return launch_conv<CONV_H2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_B2H: return launch_conv<CONV_B2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_H2F: return launch_conv<CONV_H2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_B2F: return launch_conv<CONV_B2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_F2H: return launch_conv<CONV_F2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_F2B: return launch_conv<CONV_F2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_D2F: return launch_conv<CONV_D2F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_F2D: return launch_conv<CONV_F2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_D2H: return launch_conv<CONV_D2H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_D2B: return launch_conv<CONV_D2B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_H2D: return launch_conv<CONV_H2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_B2D: return launch_conv<CONV_B2D>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E5H: return launch_conv<CONV_E5H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E5B: return launch_conv<CONV_E5B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E5F: return launch_conv<CONV_E5F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E4H: return launch_conv<CONV_E4H>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E4B: return launch_conv<CONV_E4B>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    case CONV_E4F: return launch_conv<CONV_E4F>(path, byte_aligned, descs_dev, hints_dev, n_tiles, hint_shift, raw, s);
-    default: return fail(FST_E_ARG, "unknown launch class %u", cls);
-    }
+    return launch_any_conv(conv, std::make_integer_sequence<uint32_t, CONV_COUNT>{}, path, byte_aligned, descs_dev, hints_dev, n_tiles,
+                           hint_shift, raw, s);
 }
 
 }  // namespace fst

@@ -31,32 +31,6 @@ uint32_t conv_kind(int s, int d)
     return CONV_COUNT;
 }
 
-uint32_t conv_src_bytes(uint32_t c)
-{
-    switch (c) {
-    case CONV_COPY: case CONV_E5H: case CONV_E5B: case CONV_E5F: case CONV_E4H: case CONV_E4B: case CONV_E4F: return 1;
-    case CONV_D2F: case CONV_D2H: case CONV_D2B: return 8;
-    case CONV_F2H: case CONV_F2B: case CONV_F2D: return 4;
-    default: return 2;
-    }
-}
-uint32_t conv_dst_bytes(uint32_t c)
-{
-    switch (c) {
-    case CONV_COPY: return 1;
-    case CONV_F2D: case CONV_H2D: case CONV_B2D: return 8;
-    case CONV_H2F: case CONV_B2F: case CONV_D2F: case CONV_E5F: case CONV_E4F: return 4;
-    default: return 2;
-    }
-}
-uint32_t conv_chunk_elems(uint32_t c)
-{
-    if (c == CONV_COPY) return 16;
-    // widening: what one 16-byte store holds; narrowing: 8 elements, 4 from binary64
-    if (conv_dst_bytes(c) > conv_src_bytes(c)) return 16 / conv_dst_bytes(c);
-    return conv_src_bytes(c) == 8 ? 4 : 8;
-}
-
 namespace {
 
 constexpr uint64_t kMinGroupBytes = 4096;
