@@ -507,7 +507,7 @@ def micro_cases():
         ("row segments of 4 of 32 bytes (gathered chunks; a line is fetched whole for an eighth of it)",
          specs.micro_short_rows("BF16", 16, 8), None),
         ("row segments of 8 of 16 bytes (gathered chunks)", specs.micro_short_rows("BF16", 8, 2), None),
-        ("row segments of 9 of 18 bytes (gathered chunks, byte loads)", specs.micro_short_rows("U8", 18, 2), None),
+        ("row segments of 9 of 18 bytes (gathered chunks at byte granularity, staged through LDS)", specs.micro_short_rows("U8", 18, 2), None),
         ("row segments of 2 of 16 bytes (gathered chunks)", specs.micro_short_rows("U8", 16, 8), None),
         ("4096 tensors of 8 KiB, copy", specs.micro_small_tensors(), None),
         ("4096 tensors of 8 KiB, BF16 -> F32", specs.micro_small_tensors(dst="F32"), None),

@@ -67,7 +67,7 @@ struct DevDesc {
     uint32_t div_s;          //   (0 = divisor is 1)
     uint32_t unit0;          // SPLICE, GATHER: the piece's first unit is unit `unit0` of the row at src_off
     uint32_t grain;          // GATHER: every unit's source address is a multiple of this many bytes (1, 2, 4 or 8)
-    uint32_t pad;
+    uint32_t staged;         // GATHER: 1 = the source span of every tile fits the wavefront's LDS area (see GATHER_LDS_BYTES)
 };
 static_assert(sizeof(DevDesc) == 64, "DevDesc is 64 bytes");
 
@@ -84,6 +84,7 @@ struct Piece {
     uint32_t units_per_row = 0;
     uint32_t unit0 = 0;          // SPLICE, GATHER: first unit, counted from the start of the row at src_file_off
     uint32_t grain = 1;          // GATHER: alignment every unit's source address has, by the geometry alone
+    bool staged = false;         // GATHER: tiles are read through LDS
     uint64_t src_span = 0;       // bytes from row 0 start to the end of the last row
     uint64_t read_bytes = 0, write_bytes = 0;
     // where the source bytes are staged: index of the extent inside the piece's group (for bytes
@@ -210,6 +211,17 @@ FST_HOST_DEVICE inline uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_wg)
     if (wg >= n_wg / SPAN * SPAN) return wg;             // the ragged last span keeps its order
     const uint32_t r = wg % SPAN;
     return wg - r + (r % XCD_COUNT) * XCD_RUN + r / XCD_COUNT;
+}
+// Gathered pieces whose loads would be 4 bytes or less read a tile's whole source span -- the bytes
+// from the tile's first to its last wanted byte, the other ranks' columns in between included -- with
+// coalesced 16-byte loads into an LDS area of the wavefront, and put the chunks together from there.
+// It applies when that span, rounded out to dwords, fits the area for every tile of the piece.
+constexpr uint32_t GATHER_LDS_BYTES = 4096;              // per wavefront: 64 KiB per workgroup
+inline bool gather_span_fits(uint64_t units_per_tile, uint64_t units_per_row, uint64_t unit_bytes, uint64_t stride)
+{
+    // a run of units_per_tile units that starts anywhere in a row touches at most this many rows
+    const uint64_t rows = (units_per_tile - 1) / units_per_row + 2;
+    return stride < GATHER_LDS_BYTES && 3 + (rows - 1) * stride + units_per_row * unit_bytes + 3 <= GATHER_LDS_BYTES;
 }
 // Vector pieces are cut so that chunk indices inside a piece fit 32 bits.
 constexpr uint64_t VEC_PIECE_MAX_UNITS = 1ull << 31;

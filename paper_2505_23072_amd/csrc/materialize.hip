@@ -89,6 +89,7 @@ int build_image(const fst_plan *p, size_t g0, size_t g1, void *const *out_ptrs, 
         d.units_per_row = pc->units_per_row;
         d.unit0 = pc->unit0;
         d.grain = pc->grain;
+        d.staged = pc->staged ? 1u : 0u;
         d.tile0 = r.tiles;
         d.n_tiles = tiles_of(*pc);
         if (pc->path != PATH_ELEM && pc->units_per_row) division_magic(pc->units_per_row, d.div_m, d.div_s);

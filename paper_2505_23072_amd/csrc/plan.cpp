@@ -112,6 +112,7 @@ int add_work(fst_plan *p, Group &g, uint32_t oi, uint64_t r0, uint64_t r1, uint6
             uint32_t grain = 8;
             while (grain > 1 && (addr % grain || stride % grain || (upr * unit_s) % grain)) grain /= 2;
             pc.grain = grain;
+            pc.staged = grain <= 4 && gather_span_fits(tile_units(path) * chunk, upr, unit_s, stride);
         }
         const bool chunks = path != PATH_ELEM;
         const uint64_t elems = chunks ? n_units * chunk : n_units;

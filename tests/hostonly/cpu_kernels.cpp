@@ -22,6 +22,7 @@ std::mutex g_mu;
 Range g_source{0, 0};
 std::vector<Range> g_outputs;
 uint64_t g_chunks = 0, g_violations = 0, g_direct = 0;   // g_direct: tiles whose piece took one search step at most
+uint64_t g_staged = 0;                                   // gathered tiles that went through the LDS area
 char g_first_violation[256] = "";
 
 void violation(const char *what, uint64_t a, uint64_t b)
@@ -149,6 +150,48 @@ void run_chunk(uint32_t path, bool byte_variant, const ConvInfo &ci, const fst::
     ++g_chunks;
 }
 
+// A tile of a gathered piece that goes through LDS: the wavefront reads everything from the dword of
+// the tile's first wanted byte to the dword of its last one into an area of GATHER_LDS_BYTES, and
+// every chunk is put together from bytes of that area.
+void run_staged_gather_tile(const ConvInfo &ci, const fst::DevDesc &d, const uint8_t *raw, uint32_t c0, uint32_t n)
+{
+    using namespace fst;
+    const uint32_t US = ci.cs / ci.ch, upr = d.units_per_row;
+    if (d.src_stride >= GATHER_LDS_BYTES) { violation("staged gather: stride too long", d.src_stride, 0); return; }
+    const uint32_t stride = uint32_t(d.src_stride);
+    if (uint64_t(d.unit0) + (uint64_t(c0) + n) * ci.ch > (1ull << 31)) violation("unit index beyond 2^31", d.unit0, c0);
+    const uint32_t t0 = d.unit0 + c0 * ci.ch, t1 = t0 + n * ci.ch - 1;
+    const uint32_t r0 = fast_div(t0, d.div_m, d.div_s), r1 = fast_div(t1, d.div_m, d.div_s);
+    if (r0 != t0 / upr || r1 != t1 / upr) violation("fast_div differs from the division", t0, upr);
+    const uint32_t col0 = t0 - r0 * upr, col1 = t1 - r1 * upr;
+    const uint8_t *base = raw + d.src_off;
+    const uintptr_t first = uintptr_t(base) + uint64_t(r0) * stride + col0 * US;
+    const uint8_t *from = reinterpret_cast<const uint8_t *>(first & ~uintptr_t(3));
+    const uint32_t lead = uint32_t(first) & 3u;
+    const uint32_t span = (lead + (r1 - r0) * stride + (col1 + 1 - col0) * US + 3u) & ~3u;
+    if (span > GATHER_LDS_BYTES) { violation("staged gather: the tile's span exceeds the LDS area", span, c0); return; }
+    check_read(from, span, 4, "staged gather: span outside the source");
+    if (g_violations) return;
+    std::vector<uint8_t> area(from, from + span);
+    ++g_staged;
+    for (uint32_t lane = 0; lane < n && !g_violations; ++lane) {
+        const uint32_t c = c0 + lane, u0 = d.unit0 + c * ci.ch;
+        uint8_t buf[32];
+        for (uint32_t j = 0; j < ci.ch; ++j) {
+            const uint32_t u = u0 + j, r = fast_div(u, d.div_m, d.div_s);
+            if (r != u / upr) violation("fast_div differs from the division", u, upr);
+            const uint32_t at = lead + (r - r0) * stride + (u - r * upr) * US - col0 * US;
+            if (at + US > span) { violation("staged gather: unit outside the area", at, span); return; }
+            std::memcpy(buf + j * US, area.data() + at, US);
+        }
+        uint8_t *t = reinterpret_cast<uint8_t *>(d.dst) + uint64_t(c) * ci.cd;
+        check_write(t, ci.cd, ci.cd == 8 ? 8 : 16, "chunk store outside its output or misaligned");
+        if (g_violations) return;
+        convert_and_store(ci, buf, ci.ch, t);
+        ++g_chunks;
+    }
+}
+
 void run_elem_tile(const ConvInfo &ci, const fst::DevDesc &d, const uint8_t *raw, uint32_t t)
 {
     using namespace fst;
@@ -182,7 +225,7 @@ void fst_test_clear_outputs(void)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     g_outputs.clear();
-    g_chunks = g_violations = g_direct = 0;
+    g_chunks = g_violations = g_direct = g_staged = 0;
     g_first_violation[0] = 0;
 }
 void fst_test_add_output(const void *p, uint64_t len)
@@ -192,6 +235,7 @@ void fst_test_add_output(const void *p, uint64_t len)
 }
 uint64_t fst_test_violations(void) { return g_violations; }
 uint64_t fst_test_direct_tiles(void) { return g_direct; }
+uint64_t fst_test_staged_tiles(void) { return g_staged; }
 const char *fst_test_first_violation(void) { return g_first_violation; }
 }
 
@@ -231,6 +275,7 @@ int launch_class_kernels(uint32_t cls, const DevDesc *descs, const uint32_t *hin
                 const uint32_t c0 = t * VEC_TILE_UNITS;
                 const uint32_t n = (t + 1 == d.n_tiles) ? uint32_t(d.n_units) - c0 : VEC_TILE_UNITS;
                 if (n == 0 || n > VEC_TILE_UNITS) violation("tile length", n, t);
+                if (path == PATH_GATHER && d.staged) { run_staged_gather_tile(ci, d, raw, c0, n); continue; }
                 for (uint32_t lane = 0; lane < n && !g_violations; ++lane) run_chunk(path, byte_variant, ci, d, raw, c0 + lane);
             }
         }

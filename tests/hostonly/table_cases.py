@@ -21,6 +21,7 @@ L.fst_test_add_output.argtypes = [ctypes.c_void_p, ctypes.c_uint64]
 L.fst_test_first_violation.restype = ctypes.c_char_p
 L.fst_test_violations.restype = ctypes.c_uint64
 L.fst_test_direct_tiles.restype = ctypes.c_uint64
+L.fst_test_staged_tiles.restype = ctypes.c_uint64
 
 
 def aligned(n, fill):
@@ -207,6 +208,11 @@ def test_rows_shorter_than_a_chunk(residue):
                     reqs.append((dst, len(shape) - 1, 1))
         for rank in sorted({0, world - 1}):
             check_all([blob], names, reqs, rank, world, tag=f"world {world} rank {rank}")
+            # shares of a half to a fifth of a short row go through the LDS area (an eighth's tiles span too much for it,
+            # but for the conversions with two or four elements per chunk)
+            got, plan = run([blob], names, reqs, rank, world, B.FST_LAYOUT_RESIDENT)
+            assert world > 5 or L.fst_test_staged_tiles() > 0, (world, L.fst_test_staged_tiles())
+            plan.close()
 
 
 def test_many_small_tensors_and_all_ranks():
